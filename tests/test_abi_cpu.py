@@ -1,0 +1,116 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol that
+include/l3.h declares, and its host-only entry points (encoder, header parser)
+agree with the oracle.  No GPU compute call is made here."""
+import ctypes
+import os
+import re
+import struct
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2208_08711_amd as l3
+from paper_2208_08711_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "l3.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(l3_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    assert os.path.exists(l3.library_path()), "build the library first"
+    lib = ctypes.CDLL(l3.library_path())
+    names = declared_symbols()
+    assert set(names) == set(l3.EXPORTED_SYMBOLS)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    seen = {l3.status_string(k) for k in range(8)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert l3.status_string(99) == "unknown status"
+
+
+def test_default_patch_matches_section_4_3():
+    for w, h in ((500, 375), (1079, 720), (1080, 720), (1920, 1080), (1921, 1080), (2048, 1024),
+                 (3840, 2160)):
+        assert l3.default_patch(w, h) == oracle.patch_rule(w, h)
+
+
+def test_product_encoder_matches_oracle_bytes():
+    """l3_encode_cpu is separate code from the oracle; both must produce the same file."""
+    images = synth.config1() + synth.config2(2) + [
+        synth.voronoi_scene(3, 300, 200), synth.uniform_bytes(4, 129, 70),
+        np.zeros((40, 40, 3), np.uint8), synth.gradient_noise(5, 1, 9, 2.0),
+        synth.gradient_noise(6, 9, 1, 2.0)]
+    for im in images:
+        for patch in (0, 1, 7, 32, 64, 128, 255):
+            if patch in (1, 7) and im.size > 30000:
+                continue
+            a = l3.encode_cpu(im, patch)
+            assert a == oracle.encode(im, patch), (im.shape, patch)
+            assert len(a) <= l3.encode_bound(im.shape[1], im.shape[0], patch)
+            info = l3.peek_header(a)
+            n = patch or oracle.patch_rule(im.shape[1], im.shape[0])
+            assert (info.width, info.height, info.patch) == (im.shape[1], im.shape[0], n)
+            assert info.header_bytes == 13 + 12 * info.patches_per_channel
+
+
+def test_encode_cpu_errors():
+    lib = ctypes.CDLL(l3.library_path())
+    lib.l3_encode_cpu.restype = ctypes.c_int
+    img = np.zeros((4, 4, 3), np.uint8)
+    out = np.zeros(16, np.uint8)
+    n = ctypes.c_size_t()
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    args = lambda cap, stride=12, w=4: (img.ctypes.data_as(u8p), ctypes.c_uint32(w),
+                                        ctypes.c_uint32(4), ctypes.c_size_t(stride),
+                                        ctypes.c_uint8(0), out.ctypes.data_as(u8p),
+                                        ctypes.c_size_t(cap), ctypes.byref(n))
+    assert lib.l3_encode_cpu(*args(16)) == 5          # buffer too small
+    assert lib.l3_encode_cpu(*args(16, stride=11)) == 1
+    assert lib.l3_encode_cpu(*args(16, w=0)) == 1
+    assert l3.encode_bound(0, 5) == 0
+
+
+def test_peek_header_rejects_bad_files():
+    f = bytearray(oracle.encode(synth.cosine_field(7, 100, 70), 32))
+    p = 4 * 3
+
+    def code(buf):
+        with pytest.raises(l3.L3Error) as e:
+            l3.peek_header(bytes(buf))
+        return e.value.code
+
+    assert code(f[:12]) == 3
+    assert code(f[:13 + 12 * p - 1]) == 3
+    g = bytearray(f); g[1] = 0x34
+    assert code(g) == 2
+    for pos in (4, 8):
+        g = bytearray(f); g[pos:pos + 4] = b"\0\0\0\0"
+        assert code(g) == 4
+    g = bytearray(f); g[12] = 0
+    assert code(g) == 4
+    g = bytearray(f); struct.pack_into("<I", g, 13, 1)            # first offset not 0
+    assert code(g) == 4
+    g = bytearray(f); struct.pack_into("<I", g, 13 + 8, struct.unpack_from("<I", f, 13 + 4)[0])
+    assert code(g) == 4                                           # not strictly increasing
+    g = bytearray(f); struct.pack_into("<I", g, 13 + 4 * (3 * p - 1), 0x7FFFFFF0)
+    assert code(g) == 4                                           # beyond the data section
+    assert code(f[:13 + 12 * p + struct.unpack_from("<I", f, 13 + 4 * (3 * p - 1))[0] + 2]) == 4
+    assert l3.peek_header(bytes(f)).patches_per_channel == p
+
+
+def test_context_needs_a_gpu_and_says_so():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(l3.L3Error) as e:
+        l3.Context(0)
+    assert e.value.code == 7

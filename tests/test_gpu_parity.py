@@ -1,0 +1,279 @@
+"""GPU parity: the HIP decoder, called through the C ABI, against the CPU oracle,
+byte for byte, on the same seeded inputs (arxiv 2208.08711 Sections 4.2-4.4)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2208_08711_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def l3():
+    import paper_2208_08711_amd as mod
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return mod
+
+
+@pytest.fixture(scope="module")
+def ctx(l3):
+    c = l3.Context(0)
+    yield c
+    c.close()
+
+
+def upload_files(files, misalign=True):
+    """All files in one device buffer, each at a deliberately odd offset."""
+    offs, pos = [], 0
+    for k, f in enumerate(files):
+        pos = (pos + 63) // 64 * 64 + ((1 + 3 * k) % 16 if misalign else 0)
+        offs.append(pos)
+        pos += len(f)
+    host = np.zeros(pos + 64, dtype=np.uint8)
+    for o, f in zip(offs, files):
+        host[o:o + len(f)] = np.frombuffer(f, dtype=np.uint8)
+    dev = torch.from_numpy(host).cuda()
+    return [dev[o:o + len(f)] for o, f in zip(offs, files)], dev
+
+
+def gpu_decode(l3, ctx, files, layout="hwc", poison=0xCD, pad_cols=0):
+    infos = [l3.peek_header(f) for f in files]
+    dfiles, keep = upload_files(files)
+    outs, strides = [], []
+    for inf in infos:
+        w, h = inf.width, inf.height
+        if layout == "hwc":
+            t = torch.full((h, 3 * w + pad_cols), poison, dtype=torch.uint8, device="cuda")
+            strides.append(3 * w + pad_cols)
+        else:
+            t = torch.full((3, h, w + pad_cols), poison, dtype=torch.uint8, device="cuda")
+            strides.append(w + pad_cols)
+        outs.append(t)
+    status = torch.full((len(files),), 0x55, dtype=torch.int32, device="cuda")
+    l3.decode_batch(ctx, dfiles, infos, outs, l3.LAYOUT_HWC if layout == "hwc" else l3.LAYOUT_CHW,
+                    status=status, row_strides=strides)
+    torch.cuda.synchronize()
+    res = []
+    for t, inf in zip(outs, infos):
+        a = t.cpu().numpy()
+        w, h = inf.width, inf.height
+        if layout == "hwc":
+            if pad_cols:
+                assert (a[:, 3 * w:] == poison).all(), "wrote outside the image rows"
+            res.append(a[:, :3 * w].reshape(h, w, 3))
+        else:
+            if pad_cols:
+                assert (a[:, :, w:] == poison).all(), "wrote outside the image rows"
+            res.append(a[:, :, :w].transpose(1, 2, 0))
+    return res, status.cpu().numpy()
+
+
+def check_batch(l3, ctx, images, patch=0, layout="hwc", width_mode=0, pad_cols=0):
+    files = [oracle.encode(im, patch, width_mode) for im in images]
+    got, status = gpu_decode(l3, ctx, files, layout, pad_cols=pad_cols)
+    for k, (g, f, im) in enumerate(zip(got, files, images)):
+        want = oracle.decode(f)
+        assert np.array_equal(want, im)
+        bad = np.argwhere(g != want)
+        assert bad.size == 0, (k, im.shape, patch, layout, bad[:5], len(bad))
+    assert (status == 0).all(), status
+
+
+# ---------------------------------------------------------------------------
+
+def test_config1_single_64x64(l3, ctx):
+    """configs[0]: one 64x64 gradient+noise image, N = 32."""
+    check_batch(l3, ctx, synth.config1(), layout="hwc")
+    check_batch(l3, ctx, synth.config1(), layout="chw")
+
+
+EDGE = [(1, 1), (2, 1), (1, 2), (3, 5), (4, 4), (5, 3), (31, 33), (33, 31), (32, 32), (63, 65),
+        (65, 63), (127, 3), (129, 127), (130, 129), (257, 40), (40, 257), (450, 337)]
+
+
+@pytest.mark.parametrize("patch", [32, 64, 128])
+@pytest.mark.parametrize("layout", ["hwc", "chw"])
+def test_edge_shapes(l3, ctx, patch, layout):
+    """Ragged tails in both directions, one-pixel images, widths not a multiple of the
+    pixels per lane, for every patch size of the GPU path; rows padded so that writes
+    outside the image would be seen."""
+    images = []
+    for k, (w, h) in enumerate(EDGE):
+        images.append(synth.cosine_field(700 + k, w, h))
+        images.append(synth.uniform_bytes(800 + k, w, h))
+    check_batch(l3, ctx, images, patch=patch, layout=layout, pad_cols=5)
+
+
+def test_degenerate_content(l3, ctx):
+    """All-zero, all-255, checkerboards (mod-256 wrap), constant rows (width 0)."""
+    h, w = 70, 150
+    yy, xx = np.mgrid[0:h, 0:w]
+    images = [np.zeros((h, w, 3), np.uint8), np.full((h, w, 3), 255, np.uint8),
+              (((yy + xx) & 1) * 255).astype(np.uint8)[:, :, None].repeat(3, 2),
+              ((yy & 1) * 255).astype(np.uint8)[:, :, None].repeat(3, 2),
+              (xx * 3 % 256).astype(np.uint8)[:, :, None].repeat(3, 2),
+              (yy * 5 % 256).astype(np.uint8)[:, :, None].repeat(3, 2)]
+    for patch in (32, 64, 128):
+        check_batch(l3, ctx, images, patch=patch)
+
+
+def test_non_canonical_streams(l3, ctx):
+    """Streams with non-minimal widths (always 8; minimal + 1) decode identically."""
+    images = [synth.cosine_field(31, 200, 150), synth.voronoi_scene(32, 260, 140)]
+    for mode in (1, 2):
+        for patch in (32, 128):
+            check_batch(l3, ctx, images, patch=patch, width_mode=mode)
+
+
+def test_default_patch_rule_sizes(l3, ctx):
+    """One image per class of the patch-size rule, default N."""
+    images = [synth.cosine_field(41, 500, 375), synth.voronoi_scene(42, 1280, 720),
+              synth.gradient_noise(43, 1920, 1080, 3.0), synth.voronoi_scene(44, 2048, 1024)]
+    files = [oracle.encode(im) for im in images]
+    assert [f[12] for f in files] == [32, 64, 64, 128]
+    check_batch(l3, ctx, images)
+
+
+def test_config2_variable_batch(l3, ctx):
+    """configs[1] at 24 images: variable sizes in one call, N = 32."""
+    check_batch(l3, ctx, synth.config2(24))
+    check_batch(l3, ctx, synth.config2(5), layout="chw")
+
+
+def test_config4_mixed_compressibility(l3, ctx):
+    """configs[3] at one image per half: 3840x2160, compressible and incompressible."""
+    images = [synth.gradient_noise(4000, 3840, 2160, 2.0, span=255.0),
+              synth.uniform_bytes(4004, 3840, 2160)]
+    check_batch(l3, ctx, images)
+
+
+def test_config3_full_batch_bench_configuration(l3, ctx):
+    """configs[2] at full size, the launch the benchmark times: 32 images of 2048x1024,
+    N = 128, every byte compared."""
+    check_batch(l3, ctx, synth.config3(32))
+
+
+def test_mixed_patch_sizes_in_one_call(l3, ctx):
+    images = [synth.cosine_field(51, 300, 200), synth.cosine_field(52, 300, 200),
+              synth.cosine_field(53, 300, 200)]
+    files = [oracle.encode(im, n) for im, n in zip(images, (128, 32, 64))]
+    got, status = gpu_decode(l3, ctx, files)
+    for g, im in zip(got, images):
+        assert np.array_equal(g, im)
+    assert (status == 0).all()
+
+
+def test_damaged_streams_are_flagged_and_contained(l3, ctx):
+    """A width field above 8 and a patch cut short set the image's status word; the
+    other images of the batch decode cleanly; nothing is written outside the rows."""
+    images = [synth.cosine_field(61 + k, 200, 120) for k in range(4)]
+    files = [bytearray(oracle.encode(im, 32)) for im in images]
+    hdr = 13 + 12 * (7 * 4)
+    files[1][hdr] = (files[1][hdr] & 0xF0) | 0x0D            # width 13 in the first row record
+    files[3] = files[3][:-40]                                 # last patches lose their tail
+    # the host validator accepts both (offsets are still consistent)
+    got, status = gpu_decode(l3, ctx, [bytes(f) for f in files], pad_cols=7)
+    assert status[0] == 0 and status[2] == 0
+    assert status[1] & 1
+    assert status[3] & 2
+    assert np.array_equal(got[0], images[0]) and np.array_equal(got[2], images[2])
+    # damage stays inside its patch: every other patch of image 1 is intact
+    diff = got[1] != images[1]
+    diff[0:32, 0:32, 0] = False
+    assert not diff.any()
+
+
+def test_host_errors_enqueue_nothing(l3, ctx):
+    im = synth.cosine_field(71, 100, 80)
+    f = oracle.encode(im, 16)                                  # N = 16: not a GPU patch size
+    info = l3.peek_header(f)
+    dfiles, keep = upload_files([f])
+    out = torch.zeros((80, 300), dtype=torch.uint8, device="cuda")
+    with pytest.raises(l3.L3Error) as e:
+        l3.decode_batch(ctx, dfiles, [info], [out])
+    assert e.value.code == 6
+    f = oracle.encode(im, 32)
+    info = l3.peek_header(f)
+    dfiles, keep = upload_files([f])
+    with pytest.raises(l3.L3Error) as e:                       # stride too small
+        l3.decode_batch(ctx, dfiles, [info], [out], row_strides=[299])
+    assert e.value.code == 1
+    torch.cuda.synchronize()
+    assert int(out.sum()) == 0
+    l3.decode_batch(ctx, [], [], [])                           # n = 0 is fine
+
+
+def test_many_calls_reuse_slots(l3, ctx):
+    """More calls in flight than staging slots; results stay correct."""
+    images = synth.config2(6)
+    files = [oracle.encode(im) for im in images]
+    infos = [l3.peek_header(f) for f in files]
+    dfiles, keep = upload_files(files)
+    outs = [[torch.zeros((im.shape[0], im.shape[1] * 3), dtype=torch.uint8, device="cuda")
+             for im in images] for _ in range(12)]
+    for rep in range(12):
+        l3.decode_batch(ctx, dfiles, infos, outs[rep])
+    torch.cuda.synchronize()
+    for rep in range(12):
+        for t, im in zip(outs[rep], images):
+            assert np.array_equal(t.cpu().numpy().reshape(im.shape), im)
+
+
+# ---------------------------------------------------------------------------
+# fused crop + flip + normalise (configs[4])
+
+def tensor_case(l3, ctx, images, crops, crop, dtype, patch=0):
+    files = [oracle.encode(im, patch) for im in images]
+    infos = [l3.peek_header(f) for f in files]
+    dfiles, keep = upload_files(files)
+    n = len(files)
+    out = torch.full((n, 3, crop, crop), -1, dtype=torch.int16, device="cuda")
+    status = torch.zeros(n, dtype=torch.int32, device="cuda")
+    l3.decode_crop_normalize_batch(ctx, dfiles, infos, crops, crop, crop, synth.IMAGENET_MEAN,
+                                   synth.IMAGENET_STD, out, dtype=dtype, status=status)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint16)
+    assert (status.cpu().numpy() == 0).all()
+    ftype = torch.bfloat16 if dtype == 0 else torch.float16
+    for i, (im, (x0, y0, flip)) in enumerate(zip(images, crops)):
+        want = oracle.crop_normalize(oracle.decode(files[i]), x0, y0, flip, crop, crop,
+                                     synth.IMAGENET_MEAN, synth.IMAGENET_STD, dtype)
+        a = torch.from_numpy(got[i].view(np.int16)).view(ftype).float()
+        b = torch.from_numpy(want.view(np.int16)).view(ftype).float()
+        assert float((a - b).abs().max()) <= 1e-3          # the stated tolerance
+        assert np.array_equal(got[i], want)                # and in fact identical bits
+
+
+def test_fused_crop_normalize_config5(l3, ctx):
+    """configs[4] at 32 images: 224x224 window, mirror with p = 0.5, bf16 NCHW;
+    tolerance 1e-3 absolute on the 16-bit values (they are bit-identical)."""
+    n = 32
+    shapes = synth.config2_shapes(n)
+    images = synth.config2(n)
+    crops = synth.config5_crops(shapes)
+    tensor_case(l3, ctx, images, crops, 224, 0)
+    tensor_case(l3, ctx, images[:6], crops[:6], 224, 1)
+
+
+def test_fused_crop_edges(l3, ctx):
+    """Windows touching every image border, whole-image window, larger patch sizes."""
+    im = synth.cosine_field(81, 300, 260)
+    for patch in (32, 64, 128):
+        crops = [(0, 0, 0), (300 - 224, 260 - 224, 1), (0, 260 - 224, 1), (300 - 224, 0, 0),
+                 (37, 19, 1)]
+        tensor_case(l3, ctx, [im] * len(crops), crops, 224, 0, patch=patch)
+    small = synth.cosine_field(82, 50, 40)
+    files_crop = [(0, 0, 1)]
+    # whole image as the window
+    f = oracle.encode(small, 32)
+    info = l3.peek_header(f)
+    dfiles, keep = upload_files([f])
+    out = torch.zeros((1, 3, 40, 50), dtype=torch.int16, device="cuda")
+    l3.decode_crop_normalize_batch(ctx, dfiles, [info], files_crop, 50, 40, synth.IMAGENET_MEAN,
+                                   synth.IMAGENET_STD, out)
+    torch.cuda.synchronize()
+    want = oracle.crop_normalize(small, 0, 0, 1, 50, 40, synth.IMAGENET_MEAN, synth.IMAGENET_STD, 0)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16)[0], want)
