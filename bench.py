@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the L3 batch decoder on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cityscapes|imagenet|uhd]
+
+A step is one l3_decode_batch call over one batch of synthetic images whose
+compressed files are already resident in HBM: the whole hot path (descriptor
+upload, stream staging, base-delta unpacking, inverse filter, RGB store).  The
+default workload is the Cityscapes-shaped batch the headline metric is quoted on
+(32 images of 2048x1024, N = 128).  Several input/output buffer sets are rotated
+so that consecutive steps do not hit in the last-level cache.
+
+Prints one JSON line.  `roofline.achieved` is (file bytes read + decoded bytes
+written) per launch divided by the launch time measured with events on the
+launch stream; `cpu_baseline` is the CPU oracle decoding the same files on the
+host cores (a reported baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def make_workload(name):
+    from paper_2208_08711_amd import synth
+    if name == "cityscapes":
+        return synth.config3(32), "Cityscapes-shaped: 32 RGB images 2048x1024, Voronoi regions + texture, N=128"
+    if name == "imagenet":
+        return synth.config2(256), "ImageNet-shaped: 256 RGB images 400-500 x 300-375, cosine field + noise, N=32"
+    if name == "uhd":
+        return synth.config4(8), "UHD stress: 8 RGB images 3840x2160, half compressible, half random, N=128"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="cityscapes")
+    ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (decode needs no exchange between "
+              "GPUs; see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2208_08711_amd as l3
+    import oracle                      # cpu_baseline leg and input encoding only
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (there is no CPU fallback)")
+
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+    images, label = make_workload(args.workload)
+    with ThreadPoolExecutor(cores) as pool:
+        files = list(pool.map(oracle.encode, images))
+    n = len(files)
+    file_bytes = sum(len(f) for f in files)
+    decoded_bytes = sum(im.size for im in images)
+
+    ctx = l3.Context(0)
+    infos = [l3.peek_header(f) for f in files]
+    sets = []
+    for s in range(args.sets):
+        dfiles = [torch.from_numpy(np.frombuffer(f, dtype=np.uint8).copy()).cuda() for f in files]
+        outs = [torch.empty((im.shape[0], im.shape[1] * 3), dtype=torch.uint8, device="cuda")
+                for im in images]
+        sets.append((l3.PreparedBatch(dfiles, infos, outs), outs))
+
+    stream = torch.cuda.current_stream()
+    for k in range(args.warmup):
+        l3.decode_batch_prepared(ctx, sets[k % args.sets][0], stream=stream)
+    torch.cuda.synchronize()
+
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for k in range(args.steps):
+        l3.decode_batch_prepared(ctx, sets[k % args.sets][0], stream=stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = ev0.elapsed_time(ev1)
+
+    # the result of the last steps must be the images
+    for s in range(args.sets):
+        for t, im in zip(sets[s][1], images):
+            if not np.array_equal(t.cpu().numpy().reshape(im.shape), im):
+                raise SystemExit("bench.py: decoded output differs from the input images")
+
+    ms_per_step = wall * 1e3 / args.steps
+    launch_ms = gpu_ms / args.steps
+    algo_bytes = file_bytes + decoded_bytes
+    result = {
+        "metric": "decoded images/s",
+        "value": n / (ms_per_step * 1e-3),
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": label, "batch": n, "layout": "HWC uint8",
+                   "buffer_sets_rotated": args.sets,
+                   "compressed_over_raw": round(file_bytes / decoded_bytes, 4)},
+        "decoded_GBps": decoded_bytes / (ms_per_step * 1e-3) / 1e9,
+        "hbm_fraction": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "achieved": algo_bytes / (launch_ms * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": algo_bytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "traffic": None,
+                     "kernel": "l3_decode_kernel<128,4,HWC>" if args.workload != "imagenet"
+                     else "l3_decode_kernel<32,4,HWC>",
+                     "launch_ms": launch_ms, "algorithmic_bytes_per_launch": algo_bytes},
+    }
+
+    if not args.no_cpu_baseline:
+        sample = files if args.workload != "imagenet" else files[:128]
+        sample_bytes = sum(images[i].size for i in range(len(sample)))
+        oracle.decode(sample[0])                               # warm-up
+        t = time.perf_counter()
+        for f in sample[:max(1, len(sample) // 4)]:
+            oracle.decode(f)
+        one = (time.perf_counter() - t) / max(1, len(sample) // 4)
+        with ThreadPoolExecutor(cores) as pool:
+            t = time.perf_counter()
+            list(pool.map(oracle.decode, sample))
+            many = time.perf_counter() - t
+        result["cpu_baseline"] = {
+            "value": len(sample) / many, "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": f"{len(sample)} images of the same batch, one pass over {cores} threads "
+                      f"(one image per task); single thread: {1.0 / one:.2f} images/s",
+            "decoded_GBps": sample_bytes / many / 1e9,
+            "single_thread_images_per_s": 1.0 / one,
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

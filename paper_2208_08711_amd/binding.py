@@ -194,6 +194,26 @@ def decode_batch(ctx, files, infos, outs, layout=LAYOUT_HWC, status=None, stream
                                    _stream_ptr(stream)), "l3_decode_batch")
 
 
+class PreparedBatch:
+    """Marshalled l3_item array, reusable across calls (keeps the tensors alive)."""
+
+    def __init__(self, files, infos, outs, layout=LAYOUT_HWC, row_strides=None):
+        n = len(files)
+        if row_strides is None:
+            row_strides = [int(infos[i].width) * (3 if layout == LAYOUT_HWC else 1)
+                           for i in range(n)]
+        self.n, self.layout = n, layout
+        self.items = _items(files, infos, outs, row_strides)
+        self._keep = (files, outs)
+
+
+def decode_batch_prepared(ctx, batch, status=None, stream=None):
+    """l3_decode_batch on a PreparedBatch: no per-call marshalling."""
+    _check(_load().l3_decode_batch(ctx.handle, batch.items, batch.n, batch.layout,
+                                   ctypes.c_void_p(status.data_ptr() if status is not None else None),
+                                   _stream_ptr(stream)), "l3_decode_batch")
+
+
 def decode_crop_normalize_batch(ctx, files, infos, crops, crop_w, crop_h, mean, stdv, out,
                                 dtype=BF16, status=None, stream=None):
     """crops: list of (x0, y0, flip); out: 16-bit device tensor [n, 3, crop_h, crop_w]."""
