@@ -10,7 +10,8 @@ import os
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(HERE, "libl3.so")
+# L3_LIBRARY selects another build of the same library (for experiments)
+_LIB_PATH = os.environ.get("L3_LIBRARY") or os.path.join(HERE, "libl3.so")
 
 LAYOUT_HWC, LAYOUT_CHW = 0, 1
 BF16, FP16 = 0, 1

@@ -11,21 +11,26 @@
  * How it is mapped to CDNA4 (this differs from the paper's one-block-per-patch,
  * one-thread-per-pixel CUDA decoder):
  *   - A wave (64 lanes) owns TPW horizontally adjacent patches, all three colour
- *     channels of each.  A group of LPT = N/PPL lanes owns one patch; every lane
- *     owns PPL adjacent pixels of the current row in all three channels, held as
+ *     channels of each.  A group of LPT = N/4 lanes owns one patch; every lane
+ *     owns 4 adjacent pixels of the current row in all three channels, held as
  *     packed pairs of 16-bit fields so that one v_pk_* instruction works on two
  *     pixels.  Waves never synchronise with each other.
  *   - The compressed stream of each (patch, channel) is pulled from HBM in
- *     16-byte-aligned chunks of LPT*16 bytes (one global_load_dwordx4 per lane,
- *     contiguous over the group) into a private LDS ring of two chunks, one
- *     chunk being prefetched in registers while the other is consumed.
+ *     16-byte-aligned chunks (global_load_dwordx4 per lane, contiguous over the
+ *     group) into a private LDS ring; the next chunk waits in registers.
+ *   - Rows are handled in periods of P: rings are topped up once per period for
+ *     the P rows ahead, and the P decoded rows of a period are parked in LDS and
+ *     written to HBM at the start of the next period.  Loads and stores share
+ *     one in-order counter on this hardware, so waiting for a prefetched chunk
+ *     also waits for every earlier store: the period keeps a whole period of
+ *     decode work between issuing either and waiting for them.
  *   - The row-start chain (row r+1 begins where row r ends, and row r's length
  *     is known only from its own width field) is walked in LDS by all lanes of
- *     the group redundantly (broadcast reads).
+ *     the group redundantly (broadcast reads), one row ahead of the arithmetic.
  *   - The upper-row neighbours come from registers: in-lane for the inner pixels,
  *     DPP wave shifts for the two pixels at the lane's edges.
  *   - With all three channels in one lane, interleaved RGB leaves the lane as
- *     one contiguous store of 3*PPL bytes; a wave row is a contiguous run.
+ *     one contiguous 12-byte store; a wave row is a contiguous run of 768 bytes.
  */
 #include <hip/hip_runtime.h>
 
@@ -40,33 +45,48 @@ namespace {
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
-struct __attribute__((packed, aligned(1))) U32x3u { uint32_t a, b, c; };
-struct __attribute__((packed, aligned(1))) U32u { uint32_t v; };
-struct __attribute__((packed, aligned(1))) U16u { uint16_t v; };
-struct __attribute__((packed, aligned(1))) U64u { uint64_t v; };
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+typedef u32x3 u32x3_any __attribute__((aligned(1)));      /* any byte alignment */
+typedef uint32_t u32_any __attribute__((aligned(1)));
+
+typedef __attribute__((address_space(1))) const u32x4 global_const_u32x4;
+typedef __attribute__((address_space(1))) const u32_any global_const_u32_any;
+typedef __attribute__((address_space(1))) u32x3_any global_u32x3_any;
+typedef __attribute__((address_space(1))) u32_any global_u32_any;
+typedef __attribute__((address_space(1))) uint8_t global_u8;
+typedef __attribute__((address_space(1))) uint16_t global_u16;
 
 constexpr int kWavesPerBlock = 4;
 
-template <int N, int PPL>
+template <int N>
 struct Geom {
     static_assert(N == 32 || N == 64 || N == 128, "patch sizes of the GPU path");
-    static_assert(PPL == 2 || PPL == 4, "pixels per lane");
-    static constexpr int LPT = N / PPL;          /* lanes per patch */
-    static constexpr int TPW = 64 / LPT;         /* patches per wave */
-    static constexpr int NP = PPL / 2;           /* packed registers per channel row */
-    static constexpr int CHUNK = LPT * 16;       /* bytes per refill of one stream */
-    static constexpr int RING = 2 * CHUNK;       /* ring bytes per stream */
+    static constexpr int PPL = 4;                 /* pixels per lane */
+    static constexpr int LPT = N / PPL;           /* lanes per patch */
+    static constexpr int TPW = 64 / LPT;          /* patches per wave */
+    static constexpr int NP = PPL / 2;            /* packed registers per channel row */
+    static constexpr int GPL = 2;                 /* 16-byte granules per lane per refill */
+    static constexpr int CHUNK = LPT * 16 * GPL;  /* bytes per refill of one stream (8N) */
+    static constexpr int RING = 16 * N;           /* ring bytes per stream */
     static constexpr int RING_WORDS = RING / 4 + 4; /* + 16-byte mirror of the ring start */
-    static_assert(LPT >= 1 && TPW >= 1 && CHUNK >= N + 16, "ring invariants");
+    static constexpr int P = 4;                   /* rows per period */
+    static constexpr int ROW_MAX = N + 3;         /* bytes a row can span: ceil((12 + 8N)/8) + 1 */
+    static constexpr int AHEAD = P * ROW_MAX + 12; /* bytes a period may touch past its first row */
+    /* one refill per period suffices, the first refill covers the first period
+     * from any start alignment, and a refill never overwrites bytes still needed */
+    static_assert(CHUNK >= P * ROW_MAX, "refill keeps up with the longest rows");
+    static_assert(CHUNK >= 15 + AHEAD, "first refill covers the first period");
+    static_assert(RING >= AHEAD + CHUNK + ROW_MAX + 8, "ring holds a row, a period ahead and a refill");
 };
 
 /* ---- small device helpers ------------------------------------------------ */
 
 __device__ __forceinline__ uint32_t dpp_from_lower_lane(uint32_t v) {   /* lane i <- lane i-1 */
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xF, 0xF, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
 }
 __device__ __forceinline__ uint32_t dpp_from_upper_lane(uint32_t v) {   /* lane i <- lane i+1 */
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x130 /* wave_shl:1 */, 0xF, 0xF, true);
 }
 
 __device__ __forceinline__ uint32_t pk_mad_i16(uint32_t a, uint32_t b, uint32_t c) {
@@ -102,19 +122,33 @@ __device__ __forceinline__ uint32_t predict2(uint32_t TL, uint32_t TR, uint32_t 
     return (border & T) | (~border & p);
 }
 
-/* 32 stream bits starting at bit `bit` of a ring (bit counts from the ring's
- * aligned origin; the ring holds the stream modulo RING bytes). */
+/* The 32 stream bits starting at bit `bit` of a ring live in two aligned words
+ * (bit counts from the ring's aligned origin; the ring holds the stream modulo
+ * RING bytes).  Three steps, so that the LDS address can be computed one row
+ * ahead and the read issued long before its result is needed. */
+struct RingWords { uint32_t lo, hi; };
 template <int RING>
-__device__ __forceinline__ uint32_t ring_bits(const uint32_t* ring, uint32_t bit) {
-    const uint32_t i = (bit >> 5) & (RING / 4 - 1);
-    const uint32_t lo = ring[i], hi = ring[i + 1];   /* i + 1 may be the mirror word */
-    return __builtin_amdgcn_alignbit(hi, lo, bit);   /* ({hi,lo} >> (bit & 31)) */
+__device__ __forceinline__ const uint32_t* ring_where(const uint32_t* ring, uint32_t bit) {
+    return ring + ((bit >> 5) & (RING / 4 - 1));
+}
+__device__ __forceinline__ RingWords ring_fetch(const uint32_t* where) {
+    RingWords v;
+    v.lo = where[0];
+    v.hi = where[1];   /* may be the mirror word behind the ring */
+    return v;
+}
+__device__ __forceinline__ uint32_t ring_align(RingWords v, uint32_t bit) {
+    return __builtin_amdgcn_alignbit(v.hi, v.lo, bit);   /* ({hi,lo} >> (bit & 31)) */
 }
 
-__device__ __forceinline__ uint4 load_chunk(const uint8_t* p, const uint8_t* file_end16) {
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (p < file_end16) v = *reinterpret_cast<const uint4*>(p);
+__device__ __forceinline__ u32x4 load_granule(const uint8_t* p, const uint8_t* file_end16) {
+    u32x4 v = {0, 0, 0, 0};
+    if (p < file_end16) v = *reinterpret_cast<global_const_u32x4*>((uintptr_t)p);
     return v;
+}
+
+__device__ __forceinline__ uint32_t load_u32_any_alignment(const uint8_t* p) {
+    return *reinterpret_cast<global_const_u32_any*>((uintptr_t)p);
 }
 
 __device__ __forceinline__ void wave_lds_fence() {
@@ -123,20 +157,19 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ __forceinline__ uint32_t byte_of(uint32_t packed, int k) {   /* pixel k of a packed pair */
-    return (packed >> (16 * k)) & 0xFFu;
-}
-
 /* ---- the decode kernel ---------------------------------------------------- */
 
-template <int N, int PPL, int MODE>
+template <int N, int MODE>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void l3_decode_kernel(
     const L3ImageDesc* __restrict__ descs, uint32_t* __restrict__ status, uint32_t crop_w,
     uint32_t crop_h, const uint16_t* __restrict__ lut) {
-    using G = Geom<N, PPL>;
-    constexpr int LPT = G::LPT, TPW = G::TPW, NP = G::NP, CHUNK = G::CHUNK, RING = G::RING;
+    using G = Geom<N>;
+    constexpr int PPL = G::PPL, LPT = G::LPT, TPW = G::TPW, NP = G::NP, GPL = G::GPL;
+    static_assert(NP == 2, "the row arithmetic below is written for two packed pairs per lane");
+    constexpr int CHUNK = G::CHUNK, RING = G::RING, P = G::P;
 
     __shared__ __attribute__((aligned(16))) uint32_t rings[kWavesPerBlock][TPW * 3][G::RING_WORDS];
+    __shared__ uint32_t parked[kWavesPerBlock][P][3][64];   /* decoded rows waiting for their store */
     __shared__ uint16_t s_lut[MODE == L3_MODE_TENSOR ? 768 : 2];
 
     if (MODE == L3_MODE_TENSOR) {
@@ -167,15 +200,15 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void l3_decode_kernel(
     uint32_t flags = 0;
     uint32_t bitpos[3], fill[3], endbit[3];
     const uint8_t* gaddr[3];
-    uint4 pf[3];
+    u32x4 pf[3][GPL];
     uint32_t* ring[3];
 
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
         const uint32_t flat = c * patches + ty * d.tiles_x + tx;
         const uint8_t* otab = d.file + 13 + 4 * (size_t)flat;
-        uint32_t off = reinterpret_cast<const U32u*>(otab)->v;
-        uint32_t end = flat + 1 < 3 * patches ? reinterpret_cast<const U32u*>(otab + 4)->v : data_len;
+        uint32_t off = load_u32_any_alignment(otab);
+        uint32_t end = flat + 1 < 3 * patches ? load_u32_any_alignment(otab + 4) : data_len;
         if (off > data_len || end > data_len || end < off) {
             flags |= L3_STATUS_BAD_OFFSET;
             off = min(off, data_len);
@@ -186,10 +219,25 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void l3_decode_kernel(
         bitpos[c] = (uint32_t)(a - ab) * 8;
         endbit[c] = bitpos[c] + (end - off) * 8;
         gaddr[c] = reinterpret_cast<const uint8_t*>(ab) + xl * 16;
-        fill[c] = 0;
-        pf[c] = load_chunk(gaddr[c], file_end16);
         ring[c] = rings[wave][g * 3 + c];
+#pragma unroll
+        for (int t = 0; t < GPL; ++t) pf[c][t] = load_granule(gaddr[c] + t * LPT * 16, file_end16);
     }
+    /* first chunk into the rings (covers the first period), second chunk into registers */
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+#pragma unroll
+        for (int t = 0; t < GPL; ++t) {
+            const uint32_t idx = (t * LPT + xl) * 16;
+            *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring[c]) + idx) = pf[c][t];
+            if (idx == 0) *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring[c]) + RING) = pf[c][t];
+        }
+        fill[c] = CHUNK;
+#pragma unroll
+        for (int t = 0; t < GPL; ++t)
+            pf[c][t] = load_granule(gaddr[c] + CHUNK + t * LPT * 16, file_end16);
+    }
+    wave_lds_fence();
 
     /* per-lane constants of the row loop */
     const uint32_t xpix = xl * PPL;                         /* first pixel column of this lane */
@@ -201,56 +249,147 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void l3_decode_kernel(
                     ((xb == 0 || xb + 1 == pw) ? 0xFFFF0000u : 0u);
     }
     const uint32_t nvalid = !active ? 0u : (xpix >= pw ? 0u : min((uint32_t)PPL, pw - xpix));
+    uint32_t* park = &parked[wave][0][0][lane];             /* + (slot*3 + k)*64 */
+
+    /* what the arithmetic of a row needs from its base-delta record */
+    uint32_t w[3], w2[3], w3[3], mask[3], base2[3], xbit[3], wmax = 0;
+    const uint32_t* xwhere[3];   /* LDS words holding this lane's deltas of the open row */
+    const uint32_t* hwhere[3];   /* LDS words holding the record after the open row */
+
+    /* Opens the row whose record (4-bit width, 8-bit base) is at bitpos[c]: works out
+     * where this lane's 4 deltas are (4w <= 32 contiguous bits) and advances bitpos[c]
+     * to the next record.  A width above 8 (damaged stream) is not clamped: ring
+     * indices are masked and global loads are bounded by the file, so it can only
+     * produce wrong pixels. */
+    auto open_row = [&](int c, RingWords hw) {
+        const uint32_t hdr = ring_align(hw, bitpos[c]);
+        const uint32_t wr = hdr & 15u;
+        const uint32_t base = __builtin_amdgcn_ubfe(hdr, 4, 8);
+        const uint32_t dbit = bitpos[c] + 12;
+        bitpos[c] = dbit + pw * wr;
+        xbit[c] = dbit + xpix * wr;
+        xwhere[c] = ring_where<RING>(ring[c], xbit[c]);
+        hwhere[c] = ring_where<RING>(ring[c], bitpos[c]);
+        w[c] = wr;
+        w2[c] = wr + wr;
+        w3[c] = w2[c] + wr;
+        mask[c] = (1u << wr) - 1u;
+        base2[c] = base | (base << 16);
+    };
+
+    /* Writes parked rows [first, first + count) of this wave to the output. */
+    auto flush = [&](uint32_t first, uint32_t count) {
+#pragma unroll
+        for (int i = 0; i < P; ++i) {
+            if ((uint32_t)i >= count) break;
+            const uint32_t y = y0 + first + i;
+            const uint32_t* src = park + ((first + i) % P) * 3 * 64;
+            const uint32_t o0 = src[0], o1 = src[64], o2 = src[128];
+            if (MODE == L3_MODE_HWC) {
+                uint8_t* dst = d.out + (size_t)y * d.row_stride + (size_t)(x0 + xpix) * 3;
+                if (nvalid == PPL) {
+                    const u32x3 v = {o0, o1, o2};
+#ifdef L3_EXP_NO_STORE
+                    if (o0 == 0x12345678u && o1 == 0x9abcdef0u && o2 == 77u)
+#endif
+                    *reinterpret_cast<global_u32x3_any*>((uintptr_t)dst) = v;
+                } else if (nvalid) {
+                    global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
+#pragma unroll
+                    for (int k = 0; k < 9; ++k) {
+                        const uint32_t word = k < 4 ? o0 : (k < 8 ? o1 : o2);
+                        if ((uint32_t)k < 3 * nvalid) b[k] = (uint8_t)(word >> (8 * (k & 3)));
+                    }
+                }
+            } else if (MODE == L3_MODE_CHW) {
+#pragma unroll
+                for (int c = 0; c < 3; ++c) {
+                    const uint32_t word = c == 0 ? o0 : (c == 1 ? o1 : o2);
+                    uint8_t* dst = d.out + (size_t)c * d.plane_stride + (size_t)y * d.row_stride + x0 + xpix;
+                    if (nvalid == PPL) {
+                        *reinterpret_cast<global_u32_any*>((uintptr_t)dst) = word;
+                    } else if (nvalid) {
+                        global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
+#pragma unroll
+                        for (int k = 0; k < 3; ++k)
+                            if ((uint32_t)k < nvalid) b[k] = (uint8_t)(word >> (8 * k));
+                    }
+                }
+            } else {
+                /* tensor mode: window test, optional mirror, table of the 256 normalised values */
+                const int32_t row = (int32_t)y - d.crop_y0;
+                if (row >= 0 && row < (int32_t)crop_h) {
+                    global_u16* out16 = reinterpret_cast<global_u16*>((uintptr_t)d.out);
+#pragma unroll
+                    for (int k = 0; k < PPL; ++k) {
+                        int32_t col = (int32_t)(x0 + xpix + k) - d.crop_x0;
+                        if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
+                            if (d.flip) col = (int32_t)crop_w - 1 - col;
+#pragma unroll
+                            for (int c = 0; c < 3; ++c) {
+                                const uint32_t word = c == 0 ? o0 : (c == 1 ? o1 : o2);
+                                out16[((size_t)c * crop_h + row) * crop_w + col] =
+                                    s_lut[c * 256 + ((word >> (8 * k)) & 0xFFu)];
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    };
 
     uint32_t prev[3][NP];
 #pragma unroll
-    for (int c = 0; c < 3; ++c)
+    for (int c = 0; c < 3; ++c) {
 #pragma unroll
         for (int j = 0; j < NP; ++j) prev[c][j] = 0;   /* an all-zero row above predicts 0: row 0 is raw */
+        open_row(c, ring_fetch(ring_where<RING>(ring[c], bitpos[c])));
+    }
 
     for (uint32_t r = 0; r < ph; ++r) {
-        /* keep each ring ahead of the longest possible row (12 + 8N bits) */
-#pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            const uint32_t need = (bitpos[c] >> 3) + N + 12;
-            if (fill[c] < need) {
-                const uint32_t idx = (fill[c] + xl * 16) & (RING - 1);
-                *reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(ring[c]) + idx) = pf[c];
-                if (idx == 0)
-                    *reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(ring[c]) + RING) = pf[c];
-                fill[c] += CHUNK;
-                pf[c] = load_chunk(gaddr[c] + fill[c], file_end16);
-            }
-        }
-        wave_lds_fence();
+        const uint32_t slot = r % P;
 
-        uint32_t cur[3][NP];
+        if (slot == P - 1 && r + 1 < ph) {
+            /* top the rings up for rows r+1 .. r+P; bitpos[] is the record of row r+1 */
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const uint32_t need = (bitpos[c] >> 3) + G::AHEAD;
+                if (fill[c] < need) {
+#pragma unroll
+                    for (int t = 0; t < GPL; ++t) {
+                        const uint32_t idx = (fill[c] + (t * LPT + xl) * 16) & (RING - 1);
+                        *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring[c]) + idx) = pf[c][t];
+                        if (t == 0 && idx == 0)
+                            *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring[c]) + RING) = pf[c][t];
+                    }
+                    fill[c] += CHUNK;
+#ifndef L3_EXP_NO_REFILL_LOAD
+#pragma unroll
+                    for (int t = 0; t < GPL; ++t)
+                        pf[c][t] = load_granule(gaddr[c] + fill[c] + t * LPT * 16, file_end16);
+#endif
+                }
+            }
+            wave_lds_fence();
+        }
+        if (slot == 0 && r > 0) flush(r - P, P);
+
+        /* From here to the end of the iteration there is no branch.  The deltas of
+         * row r and the record of row r+1 travel from LDS while part 1 is computed;
+         * after the last row the record read does not exist, which is harmless. */
+        RingWords hdr_next[3], xw[3];
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
-            /* base-delta record of this row: width (4 bits), base (8 bits) */
-            const uint32_t hdr = ring_bits<RING>(ring[c], bitpos[c]);
-            uint32_t w = hdr & 15u;
-            const uint32_t base = (hdr >> 4) & 255u;
-            if (w > 8) {
-                flags |= L3_STATUS_BAD_WIDTH;
-                w = 8;
-            }
-            const uint32_t dbit = bitpos[c] + 12;
-            bitpos[c] = dbit + pw * w;
-            const uint32_t base2 = base | (base << 16);
-            const uint32_t mask = (1u << w) - 1u;
-            /* this lane's PPL deltas: PPL*w <= 32 contiguous bits */
-            uint32_t x = ring_bits<RING>(ring[c], dbit + xpix * w);
-            uint32_t delta[NP];
+            xw[c] = ring_fetch(xwhere[c]);
+            hdr_next[c] = ring_fetch(hwhere[c]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        /* inverse filter, part 1: the prediction depends only on the row above
+         * (registers + lane neighbours) */
+        uint32_t pred[3][NP];
 #pragma unroll
-            for (int j = 0; j < NP; ++j) {
-                const uint32_t d0 = x & mask;
-                x >>= w;
-                const uint32_t d1 = x & mask;
-                x >>= w;
-                delta[j] = d0 | (d1 << 16);
-            }
-            /* inverse filter from the row above (registers + lane neighbours) */
+        for (int c = 0; c < 3; ++c) {
             const uint32_t from_left = dpp_from_lower_lane(prev[c][NP - 1]);
             const uint32_t from_right = dpp_from_upper_lane(prev[c][0]);
 #pragma unroll
@@ -259,87 +398,61 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void l3_decode_kernel(
                 const uint32_t TL = __builtin_amdgcn_alignbit(T, j > 0 ? prev[c][j - 1] : from_left, 16);
                 const uint32_t TR =
                     __builtin_amdgcn_alignbit(j < NP - 1 ? prev[c][j + 1] : from_right, T, 16);
-                const uint32_t pred = predict2(TL, TR, T, border[j]);
-                cur[c][j] = (pred + delta[j] + base2) & 0x00FF00FFu;
+                pred[c][j] = predict2(TL, TR, T, border[j]);
             }
         }
 
-        /* store the row */
-        const uint32_t y = y0 + r;
+        __builtin_amdgcn_sched_barrier(0);
+        /* base-delta: value = base + delta; part 2 of the filter: pixel = prediction
+         * + value (both mod 256, one mask at the end) */
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            wmax = max(wmax, w[c]);
+            const uint32_t x = ring_align(xw[c], xbit[c]);
+            const uint32_t d0 = x & mask[c];
+            const uint32_t d1 = __builtin_amdgcn_ubfe(x, w[c], w[c]);
+            const uint32_t d2 = __builtin_amdgcn_ubfe(x, w2[c], w[c]);
+            const uint32_t d3 = __builtin_amdgcn_ubfe(x, w3[c], w[c]);
+            prev[c][0] = (pred[c][0] + (d0 | (d1 << 16)) + base2[c]) & 0x00FF00FFu;
+            prev[c][1] = (pred[c][1] + (d2 | (d3 << 16)) + base2[c]) & 0x00FF00FFu;
+        }
+
+        /* park the row: bytes in output order */
+        uint32_t o0, o1, o2;
         if (MODE == L3_MODE_HWC) {
-            uint8_t* dst = d.out + (size_t)y * d.row_stride + (size_t)(x0 + xpix) * 3;
-            if (nvalid == PPL) {
-                if (PPL == 4) {
-                    U32x3u v;
-                    v.a = byte_of(cur[0][0], 0) | (byte_of(cur[1][0], 0) << 8) |
-                          (byte_of(cur[2][0], 0) << 16) | (byte_of(cur[0][0], 1) << 24);
-                    v.b = byte_of(cur[1][0], 1) | (byte_of(cur[2][0], 1) << 8) |
-                          (byte_of(cur[0][NP - 1], 0) << 16) | (byte_of(cur[1][NP - 1], 0) << 24);
-                    v.c = byte_of(cur[2][NP - 1], 0) | (byte_of(cur[0][NP - 1], 1) << 8) |
-                          (byte_of(cur[1][NP - 1], 1) << 16) | (byte_of(cur[2][NP - 1], 1) << 24);
-                    *reinterpret_cast<U32x3u*>(dst) = v;
-                } else {
-                    const uint32_t a = byte_of(cur[0][0], 0) | (byte_of(cur[1][0], 0) << 8) |
-                                       (byte_of(cur[2][0], 0) << 16) | (byte_of(cur[0][0], 1) << 24);
-                    const uint32_t b = byte_of(cur[1][0], 1) | (byte_of(cur[2][0], 1) << 8);
-                    reinterpret_cast<U32u*>(dst)->v = a;
-                    reinterpret_cast<U16u*>(dst + 4)->v = (uint16_t)b;
-                }
-            } else {
-#pragma unroll
-                for (int k = 0; k < PPL; ++k)
-                    if ((uint32_t)k < nvalid) {
-#pragma unroll
-                        for (int c = 0; c < 3; ++c) dst[3 * k + c] = (uint8_t)byte_of(cur[c][k >> 1], k & 1);
-                    }
-            }
-        } else if (MODE == L3_MODE_CHW) {
-#pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                uint8_t* dst = d.out + (size_t)c * d.plane_stride + (size_t)y * d.row_stride + x0 + xpix;
-                if (nvalid == PPL) {
-                    if (PPL == 4) {
-                        reinterpret_cast<U32u*>(dst)->v =
-                            byte_of(cur[c][0], 0) | (byte_of(cur[c][0], 1) << 8) |
-                            (byte_of(cur[c][NP - 1], 0) << 16) | (byte_of(cur[c][NP - 1], 1) << 24);
-                    } else {
-                        reinterpret_cast<U16u*>(dst)->v =
-                            (uint16_t)(byte_of(cur[c][0], 0) | (byte_of(cur[c][0], 1) << 8));
-                    }
-                } else {
-#pragma unroll
-                    for (int k = 0; k < PPL; ++k)
-                        if ((uint32_t)k < nvalid) dst[k] = (uint8_t)byte_of(cur[c][k >> 1], k & 1);
-                }
-            }
+            /* R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3 */
+            const uint32_t t0 = __builtin_amdgcn_perm(prev[1][0], prev[0][0], 0x020c0400u);
+            o0 = __builtin_amdgcn_perm(prev[2][0], t0, 0x03040100u);
+            const uint32_t t1 = __builtin_amdgcn_perm(prev[2][0], prev[1][0], 0x0c0c0602u);
+            const uint32_t t2 = __builtin_amdgcn_perm(prev[1][1], prev[0][1], 0x04000c0cu);
+            o1 = t1 | t2;
+            const uint32_t t3 = __builtin_amdgcn_perm(prev[0][1], prev[2][1], 0x020c0600u);
+            o2 = __builtin_amdgcn_perm(prev[1][1], t3, 0x03060100u);
         } else {
-            /* tensor mode: window test, optional mirror, table of the 256 normalised values */
-            const int32_t row = (int32_t)y - d.crop_y0;
-            if (row >= 0 && row < (int32_t)crop_h) {
-                uint16_t* out16 = reinterpret_cast<uint16_t*>(d.out);
-#pragma unroll
-                for (int k = 0; k < PPL; ++k) {
-                    int32_t col = (int32_t)(x0 + xpix + k) - d.crop_x0;
-                    if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
-                        if (d.flip) col = (int32_t)crop_w - 1 - col;
-#pragma unroll
-                        for (int c = 0; c < 3; ++c)
-                            out16[((size_t)c * crop_h + row) * crop_w + col] =
-                                s_lut[c * 256 + byte_of(cur[c][k >> 1], k & 1)];
-                    }
-                }
-            }
+            /* one word per channel: p0 p1 p2 p3 */
+            o0 = __builtin_amdgcn_perm(prev[0][1], prev[0][0], 0x06040200u);
+            o1 = __builtin_amdgcn_perm(prev[1][1], prev[1][0], 0x06040200u);
+            o2 = __builtin_amdgcn_perm(prev[2][1], prev[2][0], 0x06040200u);
         }
+        park[(slot * 3 + 0) * 64] = o0;
+        park[(slot * 3 + 1) * 64] = o1;
+        park[(slot * 3 + 2) * 64] = o2;
 
+        /* open row r+1 */
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int c = 0; c < 3; ++c)
-#pragma unroll
-            for (int j = 0; j < NP; ++j) prev[c][j] = cur[c][j];
+        for (int c = 0; c < 3; ++c) open_row(c, hdr_next[c]);
+    }
+    {
+        const uint32_t first = ((ph - 1) / P) * P;
+        flush(first, ph - first);
     }
 
+    if (wmax > 8) flags |= L3_STATUS_BAD_WIDTH;
+    /* bitpos[] is one (non-existent) row past the end: step back over it */
 #pragma unroll
     for (int c = 0; c < 3; ++c)
-        if (bitpos[c] > endbit[c]) flags |= L3_STATUS_OVERRUN;
+        if (bitpos[c] - 12 - pw * w[c] > endbit[c]) flags |= L3_STATUS_OVERRUN;
     if (flags && active && status) atomicOr(&status[d.status_index], flags);
 }
 
@@ -378,34 +491,21 @@ __global__ void l3_fill_u32_kernel(uint32_t* p, uint32_t n, uint32_t value) {
 
 constexpr int kSlots = 4;   /* descriptor staging slots: calls in flight before the host waits */
 
-int pixels_per_lane() {
-    static int v = [] {
-        const char* e = std::getenv("L3_PIXELS_PER_LANE");
-        return (e && e[0] == '2' && e[1] == 0) ? 2 : 4;
-    }();
-    return v;
-}
-
 typedef void (*decode_kernel_t)(const L3ImageDesc*, uint32_t*, uint32_t, uint32_t, const uint16_t*);
 
-template <int N, int PPL>
+template <int N>
 decode_kernel_t kernel_for_mode(int mode) {
     switch (mode) {
-        case L3_MODE_HWC: return l3_decode_kernel<N, PPL, L3_MODE_HWC>;
-        case L3_MODE_CHW: return l3_decode_kernel<N, PPL, L3_MODE_CHW>;
-        default: return l3_decode_kernel<N, PPL, L3_MODE_TENSOR>;
+        case L3_MODE_HWC: return l3_decode_kernel<N, L3_MODE_HWC>;
+        case L3_MODE_CHW: return l3_decode_kernel<N, L3_MODE_CHW>;
+        default: return l3_decode_kernel<N, L3_MODE_TENSOR>;
     }
 }
 
-decode_kernel_t pick_kernel(int n, int ppl, int mode, int* tiles_per_wave) {
-    if (ppl == 2) {
-        if (n == 32) { *tiles_per_wave = Geom<32, 2>::TPW; return kernel_for_mode<32, 2>(mode); }
-        if (n == 64) { *tiles_per_wave = Geom<64, 2>::TPW; return kernel_for_mode<64, 2>(mode); }
-        *tiles_per_wave = Geom<128, 2>::TPW; return kernel_for_mode<128, 2>(mode);
-    }
-    if (n == 32) { *tiles_per_wave = Geom<32, 4>::TPW; return kernel_for_mode<32, 4>(mode); }
-    if (n == 64) { *tiles_per_wave = Geom<64, 4>::TPW; return kernel_for_mode<64, 4>(mode); }
-    *tiles_per_wave = Geom<128, 4>::TPW; return kernel_for_mode<128, 4>(mode);
+decode_kernel_t pick_kernel(int n, int mode, int* tiles_per_wave) {
+    if (n == 32) { *tiles_per_wave = Geom<32>::TPW; return kernel_for_mode<32>(mode); }
+    if (n == 64) { *tiles_per_wave = Geom<64>::TPW; return kernel_for_mode<64>(mode); }
+    *tiles_per_wave = Geom<128>::TPW; return kernel_for_mode<128>(mode);
 }
 
 }  // namespace
@@ -416,7 +516,9 @@ struct l3_ctx {
     L3ImageDesc* h_stage[kSlots] = {};    /* pinned host */
     L3ImageDesc* d_descs[kSlots] = {};    /* device */
     uint16_t* d_table[kSlots] = {};       /* device: 768-entry normalisation table */
-    hipEvent_t done[kSlots] = {};
+    hipEvent_t done[kSlots] = {};         /* the slot's kernels have finished */
+    hipEvent_t copied[kSlots] = {};       /* the slot's descriptors are on the device */
+    hipStream_t copy_stream = nullptr;    /* descriptor uploads overlap the previous call's kernels */
     bool pending[kSlots] = {};
     int next = 0;
 };
@@ -513,13 +615,12 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     /* descriptors grouped by patch size: classes 32, 64, 128 in this order */
     static const int kClasses[3] = {32, 64, 128};
     int class_begin[4] = {0, 0, 0, 0};
-    const int ppl = pixels_per_lane();
     int filled = 0;
     uint32_t max_units[3] = {0, 0, 0};
     for (int k = 0; k < 3; ++k) {
         class_begin[k] = filled;
         int tpw = 1;
-        (void)pick_kernel(kClasses[k], ppl, mode, &tpw);
+        (void)pick_kernel(kClasses[k], mode, &tpw);
         for (int i = 0; i < n; ++i) {
             if (k == 0) {   /* validate everything before anything is enqueued */
                 L3ImageDesc probe;
@@ -571,7 +672,9 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
 
     L3ImageDesc* d_descs = ctx->d_descs[slot];
     if (hipMemcpyAsync(d_descs, stage, (size_t)n * sizeof(L3ImageDesc), hipMemcpyHostToDevice,
-                       stream) != hipSuccess)
+                       ctx->copy_stream) != hipSuccess ||
+        hipEventRecord(ctx->copied[slot], ctx->copy_stream) != hipSuccess ||
+        hipStreamWaitEvent(stream, ctx->copied[slot], 0) != hipSuccess)
         return L3_ERR_DEVICE;
     if (d_status)
         hipLaunchKernelGGL(l3_fill_u32_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, d_status,
@@ -586,7 +689,7 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         const int count = class_begin[k + 1] - class_begin[k];
         if (count == 0 || max_units[k] == 0) continue;
         int tpw = 1;
-        decode_kernel_t kern = pick_kernel(kClasses[k], ppl, mode, &tpw);
+        decode_kernel_t kern = pick_kernel(kClasses[k], mode, &tpw);
         const uint32_t gx = (max_units[k] + kWavesPerBlock - 1) / kWavesPerBlock;
         for (int first = 0; first < count; first += 65535) {
             const int m = count - first < 65535 ? count - first : 65535;
@@ -615,8 +718,14 @@ l3_status l3_ctx_create(l3_ctx** out, int device) {
     l3_ctx* ctx = new (std::nothrow) l3_ctx;
     if (!ctx) return L3_ERR_DEVICE;
     ctx->device = device;
+    if (hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking) != hipSuccess) {
+        ctx->copy_stream = nullptr;
+        l3_ctx_destroy(ctx);
+        return L3_ERR_DEVICE;
+    }
     for (int s = 0; s < kSlots; ++s) {
         if (hipEventCreateWithFlags(&ctx->done[s], hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&ctx->copied[s], hipEventDisableTiming) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&ctx->d_table[s]), 768 * sizeof(uint16_t)) !=
                 hipSuccess) {
             l3_ctx_destroy(ctx);
@@ -633,7 +742,12 @@ void l3_ctx_destroy(l3_ctx* ctx) {
     for (int s = 0; s < kSlots; ++s) {
         if (ctx->pending[s]) (void)hipEventSynchronize(ctx->done[s]);
         if (ctx->done[s]) (void)hipEventDestroy(ctx->done[s]);
+        if (ctx->copied[s]) (void)hipEventDestroy(ctx->copied[s]);
         if (ctx->d_table[s]) (void)hipFree(ctx->d_table[s]);
+    }
+    if (ctx->copy_stream) {
+        (void)hipStreamSynchronize(ctx->copy_stream);
+        (void)hipStreamDestroy(ctx->copy_stream);
     }
     release_slots(ctx);
     delete ctx;
