@@ -10,27 +10,27 @@
  *
  * How it is mapped to CDNA4 (this differs from the paper's one-block-per-patch,
  * one-thread-per-pixel CUDA decoder):
- *   - A wave (64 lanes) owns TPW horizontally adjacent patches, all three colour
- *     channels of each.  A group of LPT = N/4 lanes owns one patch; every lane
- *     owns 4 adjacent pixels of the current row in all three channels, held as
- *     packed pairs of 16-bit fields so that one v_pk_* instruction works on two
- *     pixels.  Waves never synchronise with each other.
+ *   - A workgroup of three waves owns TPW horizontally adjacent patches; wave c
+ *     decodes colour channel c of all of them.  A group of LPT = N/4 lanes owns
+ *     one patch; every lane owns 4 adjacent pixels of the current row, held as
+ *     two packed pairs of 16-bit fields so that one v_pk_* instruction works on
+ *     two pixels.
  *   - The compressed stream of each (patch, channel) is pulled from HBM in
  *     16-byte-aligned chunks (global_load_dwordx4 per lane, contiguous over the
  *     group) into a private LDS ring; the next chunk waits in registers.
- *   - Rows are handled in periods of P: rings are topped up once per period for
- *     the P rows ahead, and the P decoded rows of a period are parked in LDS and
- *     written to HBM at the start of the next period.  Loads and stores share
- *     one in-order counter on this hardware, so waiting for a prefetched chunk
- *     also waits for every earlier store: the period keeps a whole period of
- *     decode work between issuing either and waiting for them.
+ *   - Rows are handled in periods of P = 3: rings are topped up once per period
+ *     for the P rows ahead; the P decoded rows of a period are parked in LDS (one
+ *     word of 4 pixels per lane and channel), and after one workgroup barrier
+ *     per period wave c interleaves the three channels of row c of the period
+ *     and writes it to HBM (12 contiguous bytes per lane, 768 per wave row).
+ *     Loads and stores share one in-order counter on this hardware, so waiting
+ *     for a prefetched chunk also waits for every earlier store: the period
+ *     keeps rows of decode work between issuing either and waiting for them.
  *   - The row-start chain (row r+1 begins where row r ends, and row r's length
  *     is known only from its own width field) is walked in LDS by all lanes of
  *     the group redundantly (broadcast reads), one row ahead of the arithmetic.
  *   - The upper-row neighbours come from registers: in-lane for the inner pixels,
  *     DPP wave shifts for the two pixels at the lane's edges.
- *   - With all three channels in one lane, interleaved RGB leaves the lane as
- *     one contiguous 12-byte store; a wave row is a contiguous run of 768 bytes.
  */
 #include <hip/hip_runtime.h>
 
@@ -57,7 +57,7 @@ typedef __attribute__((address_space(1))) u32_any global_u32_any;
 typedef __attribute__((address_space(1))) uint8_t global_u8;
 typedef __attribute__((address_space(1))) uint16_t global_u16;
 
-constexpr int kWavesPerBlock = 4;
+constexpr int kBlockThreads = 192;   /* three waves: one per colour channel */
 
 template <int N>
 struct Geom {
@@ -65,12 +65,11 @@ struct Geom {
     static constexpr int PPL = 4;                 /* pixels per lane */
     static constexpr int LPT = N / PPL;           /* lanes per patch */
     static constexpr int TPW = 64 / LPT;          /* patches per wave */
-    static constexpr int NP = PPL / 2;            /* packed registers per channel row */
     static constexpr int GPL = 2;                 /* 16-byte granules per lane per refill */
     static constexpr int CHUNK = LPT * 16 * GPL;  /* bytes per refill of one stream (8N) */
     static constexpr int RING = 16 * N;           /* ring bytes per stream */
     static constexpr int RING_WORDS = RING / 4 + 4; /* + 16-byte mirror of the ring start */
-    static constexpr int P = 4;                   /* rows per period */
+    static constexpr int P = 3;                   /* rows per period = waves per workgroup */
     static constexpr int ROW_MAX = N + 3;         /* bytes a row can span: ceil((12 + 8N)/8) + 1 */
     static constexpr int AHEAD = P * ROW_MAX + 12; /* bytes a period may touch past its first row */
     /* one refill per period suffices, the first refill covers the first period
@@ -82,10 +81,10 @@ struct Geom {
 
 /* ---- small device helpers ------------------------------------------------ */
 
-__device__ __forceinline__ uint32_t dpp_from_lower_lane(uint32_t v) {   /* lane i <- lane i-1 */
+__device__ __forceinline__ uint32_t dpp_from_lower_lane(uint32_t v) {   /* lane i <- lane i-1, lane 0 <- 0 */
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
 }
-__device__ __forceinline__ uint32_t dpp_from_upper_lane(uint32_t v) {   /* lane i <- lane i+1 */
+__device__ __forceinline__ uint32_t dpp_from_upper_lane(uint32_t v) {   /* lane i <- lane i+1, lane 63 <- 0 */
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x130 /* wave_shl:1 */, 0xF, 0xF, true);
 }
 
@@ -160,28 +159,26 @@ __device__ __forceinline__ void wave_lds_fence() {
 /* ---- the decode kernel ---------------------------------------------------- */
 
 template <int N, int MODE>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void l3_decode_kernel(
-    const L3ImageDesc* __restrict__ descs, uint32_t* __restrict__ status, uint32_t crop_w,
-    uint32_t crop_h, const uint16_t* __restrict__ lut) {
+__device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __restrict__ status,
+                                            uint32_t crop_w, uint32_t crop_h,
+                                            const uint16_t* __restrict__ lut) {
     using G = Geom<N>;
-    constexpr int PPL = G::PPL, LPT = G::LPT, TPW = G::TPW, NP = G::NP, GPL = G::GPL;
-    static_assert(NP == 2, "the row arithmetic below is written for two packed pairs per lane");
+    constexpr int PPL = G::PPL, LPT = G::LPT, TPW = G::TPW, GPL = G::GPL;
     constexpr int CHUNK = G::CHUNK, RING = G::RING, P = G::P;
 
-    __shared__ __attribute__((aligned(16))) uint32_t rings[kWavesPerBlock][TPW * 3][G::RING_WORDS];
-    __shared__ uint32_t parked[kWavesPerBlock][P][3][64];   /* decoded rows waiting for their store */
+    __shared__ __attribute__((aligned(16))) uint32_t rings[3][TPW][G::RING_WORDS];
+    __shared__ uint32_t parked[2][P][3][64];   /* [buffer][row of period][channel][lane] */
     __shared__ uint16_t s_lut[MODE == L3_MODE_TENSOR ? 768 : 2];
 
     if (MODE == L3_MODE_TENSOR) {
-        for (uint32_t i = threadIdx.x; i < 768; i += 64 * kWavesPerBlock) s_lut[i] = lut[i];
+        for (uint32_t i = threadIdx.x; i < 768; i += kBlockThreads) s_lut[i] = lut[i];
         __syncthreads();
     }
 
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const L3ImageDesc& d = descs[blockIdx.y];
-    const uint32_t unit = blockIdx.x * kWavesPerBlock + wave;
-    if (unit >= d.units) return;
+    const uint32_t c = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   /* this wave's channel */
+    const uint32_t unit = blockIdx.x;
+    if (unit >= d.units) return;                                           /* whole workgroup */
 
     const uint32_t g = lane / LPT, xl = lane % LPT;
     const uint32_t trow = unit / d.groups_x, gx = unit - trow * d.groups_x;
@@ -191,20 +188,19 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void l3_decode_kernel(
     const uint32_t tx = d.tile_x_first + (active ? txr : d.tile_x_count - 1);
     const uint32_t x0 = tx * N, y0 = ty * N;
     const uint32_t pw = min((uint32_t)N, d.width - x0);
-    const uint32_t ph = min((uint32_t)N, d.height - y0);     /* same for the whole wave */
+    const uint32_t ph = min((uint32_t)N, d.height - y0);     /* same for the whole workgroup */
     const uint32_t patches = d.tiles_x * d.tiles_y;
     const uint32_t data_len = (uint32_t)(d.file_len - d.header_bytes);
     const uint8_t* file_end16 =
         reinterpret_cast<const uint8_t*>(((uintptr_t)d.file + d.file_len + 15) & ~(uintptr_t)15);
 
+    /* locate this lane group's stream: Section 4.3, offset array of channel c */
     uint32_t flags = 0;
-    uint32_t bitpos[3], fill[3], endbit[3];
-    const uint8_t* gaddr[3];
-    u32x4 pf[3][GPL];
-    uint32_t* ring[3];
-
-#pragma unroll
-    for (int c = 0; c < 3; ++c) {
+    uint32_t bitpos, endbit, fill;
+    const uint8_t* gaddr;
+    u32x4 pf[GPL];
+    uint32_t* const ring = rings[c][g];
+    {
         const uint32_t flat = c * patches + ty * d.tiles_x + tx;
         const uint8_t* otab = d.file + 13 + 4 * (size_t)flat;
         uint32_t off = load_u32_any_alignment(otab);
@@ -216,121 +212,116 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void l3_decode_kernel(
         }
         const uintptr_t a = (uintptr_t)(d.file + d.header_bytes + off);
         const uintptr_t ab = a & ~(uintptr_t)15;
-        bitpos[c] = (uint32_t)(a - ab) * 8;
-        endbit[c] = bitpos[c] + (end - off) * 8;
-        gaddr[c] = reinterpret_cast<const uint8_t*>(ab) + xl * 16;
-        ring[c] = rings[wave][g * 3 + c];
+        bitpos = (uint32_t)(a - ab) * 8;
+        endbit = bitpos + (end - off) * 8;
+        gaddr = reinterpret_cast<const uint8_t*>(ab) + xl * 16;
+        /* first chunk into the ring (covers the first period), second into registers */
 #pragma unroll
-        for (int t = 0; t < GPL; ++t) pf[c][t] = load_granule(gaddr[c] + t * LPT * 16, file_end16);
-    }
-    /* first chunk into the rings (covers the first period), second chunk into registers */
-#pragma unroll
-    for (int c = 0; c < 3; ++c) {
+        for (int t = 0; t < GPL; ++t) pf[t] = load_granule(gaddr + t * LPT * 16, file_end16);
 #pragma unroll
         for (int t = 0; t < GPL; ++t) {
             const uint32_t idx = (t * LPT + xl) * 16;
-            *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring[c]) + idx) = pf[c][t];
-            if (idx == 0) *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring[c]) + RING) = pf[c][t];
+            *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + idx) = pf[t];
+            if (idx == 0) *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + RING) = pf[t];
         }
-        fill[c] = CHUNK;
+        fill = CHUNK;
 #pragma unroll
-        for (int t = 0; t < GPL; ++t)
-            pf[c][t] = load_granule(gaddr[c] + CHUNK + t * LPT * 16, file_end16);
+        for (int t = 0; t < GPL; ++t) pf[t] = load_granule(gaddr + CHUNK + t * LPT * 16, file_end16);
     }
     wave_lds_fence();
 
     /* per-lane constants of the row loop */
     const uint32_t xpix = xl * PPL;                         /* first pixel column of this lane */
-    uint32_t border[NP];
+    uint32_t border[2];
 #pragma unroll
-    for (int j = 0; j < NP; ++j) {
+    for (int j = 0; j < 2; ++j) {
         const uint32_t xa = xpix + 2 * j, xb = xa + 1;
         border[j] = ((xa == 0 || xa + 1 == pw) ? 0x0000FFFFu : 0u) |
                     ((xb == 0 || xb + 1 == pw) ? 0xFFFF0000u : 0u);
     }
     const uint32_t nvalid = !active ? 0u : (xpix >= pw ? 0u : min((uint32_t)PPL, pw - xpix));
-    uint32_t* park = &parked[wave][0][0][lane];             /* + (slot*3 + k)*64 */
 
     /* what the arithmetic of a row needs from its base-delta record */
-    uint32_t w[3], w2[3], w3[3], mask[3], base2[3], xbit[3], wmax = 0;
-    const uint32_t* xwhere[3];   /* LDS words holding this lane's deltas of the open row */
-    const uint32_t* hwhere[3];   /* LDS words holding the record after the open row */
+    uint32_t w, w2, w3, base2, xbit, wmax = 0;
+    const uint32_t* xwhere;   /* LDS words holding this lane's deltas of the open row */
+    const uint32_t* hwhere;   /* LDS words holding the record after the open row */
 
-    /* Opens the row whose record (4-bit width, 8-bit base) is at bitpos[c]: works out
-     * where this lane's 4 deltas are (4w <= 32 contiguous bits) and advances bitpos[c]
+    /* Opens the row whose record (4-bit width, 8-bit base) is at bitpos: works out
+     * where this lane's 4 deltas are (4w <= 32 contiguous bits) and advances bitpos
      * to the next record.  A width above 8 (damaged stream) is not clamped: ring
      * indices are masked and global loads are bounded by the file, so it can only
      * produce wrong pixels. */
-    auto open_row = [&](int c, RingWords hw) {
-        const uint32_t hdr = ring_align(hw, bitpos[c]);
+    auto open_row = [&](RingWords hw) {
+        const uint32_t hdr = ring_align(hw, bitpos);
         const uint32_t wr = hdr & 15u;
         const uint32_t base = __builtin_amdgcn_ubfe(hdr, 4, 8);
-        const uint32_t dbit = bitpos[c] + 12;
-        bitpos[c] = dbit + pw * wr;
-        xbit[c] = dbit + xpix * wr;
-        xwhere[c] = ring_where<RING>(ring[c], xbit[c]);
-        hwhere[c] = ring_where<RING>(ring[c], bitpos[c]);
-        w[c] = wr;
-        w2[c] = wr + wr;
-        w3[c] = w2[c] + wr;
-        mask[c] = (1u << wr) - 1u;
-        base2[c] = base | (base << 16);
+        const uint32_t dbit = bitpos + 12;
+        bitpos = dbit + pw * wr;
+        xbit = dbit + xpix * wr;
+        xwhere = ring_where<RING>(ring, xbit);
+        hwhere = ring_where<RING>(ring, bitpos);
+        w = wr;
+        w2 = wr + wr;
+        w3 = w2 + wr;
+        base2 = base | (base << 16);
     };
 
-    /* Writes parked rows [first, first + count) of this wave to the output. */
-    auto flush = [&](uint32_t first, uint32_t count) {
+    /* After the workgroup barrier: this wave writes row c of the period whose rows
+     * are parked in buffer `buf` (rows first .. first+count-1 of the patch). */
+    auto flush = [&](uint32_t buf, uint32_t first, uint32_t count) {
+        if (c >= count) return;
+        const uint32_t y = y0 + first + c;
+        const uint32_t* src = &parked[buf][c][0][lane];
+        const uint32_t pr = src[0], pg = src[64], pb = src[128];   /* 4 pixels of R, G, B */
+        if (MODE == L3_MODE_HWC) {
+            uint8_t* dst = d.out + (size_t)y * d.row_stride + (size_t)(x0 + xpix) * 3;
+            /* R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3 */
+            const uint32_t t0 = __builtin_amdgcn_perm(pg, pr, 0x010c0400u);
+            const uint32_t o0 = __builtin_amdgcn_perm(pb, t0, 0x03040100u);
+            const uint32_t t1 = __builtin_amdgcn_perm(pb, pg, 0x020c0501u);
+            const uint32_t o1 = __builtin_amdgcn_perm(pr, t1, 0x03060100u);
+            const uint32_t t2 = __builtin_amdgcn_perm(pr, pb, 0x030c0702u);
+            const uint32_t o2 = __builtin_amdgcn_perm(pg, t2, 0x03070100u);
+            if (nvalid == PPL) {
+                const u32x3 v = {o0, o1, o2};
+                *reinterpret_cast<global_u32x3_any*>((uintptr_t)dst) = v;
+            } else if (nvalid) {
+                global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
 #pragma unroll
-        for (int i = 0; i < P; ++i) {
-            if ((uint32_t)i >= count) break;
-            const uint32_t y = y0 + first + i;
-            const uint32_t* src = park + ((first + i) % P) * 3 * 64;
-            const uint32_t o0 = src[0], o1 = src[64], o2 = src[128];
-            if (MODE == L3_MODE_HWC) {
-                uint8_t* dst = d.out + (size_t)y * d.row_stride + (size_t)(x0 + xpix) * 3;
+                for (int k = 0; k < 9; ++k) {
+                    const uint32_t word = k < 4 ? o0 : (k < 8 ? o1 : o2);
+                    if ((uint32_t)k < 3 * nvalid) b[k] = (uint8_t)(word >> (8 * (k & 3)));
+                }
+            }
+        } else if (MODE == L3_MODE_CHW) {
+#pragma unroll
+            for (int ch = 0; ch < 3; ++ch) {
+                const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
+                uint8_t* dst = d.out + (size_t)ch * d.plane_stride + (size_t)y * d.row_stride + x0 + xpix;
                 if (nvalid == PPL) {
-                    const u32x3 v = {o0, o1, o2};
-#ifdef L3_EXP_NO_STORE
-                    if (o0 == 0x12345678u && o1 == 0x9abcdef0u && o2 == 77u)
-#endif
-                    *reinterpret_cast<global_u32x3_any*>((uintptr_t)dst) = v;
+                    *reinterpret_cast<global_u32_any*>((uintptr_t)dst) = word;
                 } else if (nvalid) {
                     global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
 #pragma unroll
-                    for (int k = 0; k < 9; ++k) {
-                        const uint32_t word = k < 4 ? o0 : (k < 8 ? o1 : o2);
-                        if ((uint32_t)k < 3 * nvalid) b[k] = (uint8_t)(word >> (8 * (k & 3)));
-                    }
+                    for (int k = 0; k < 3; ++k)
+                        if ((uint32_t)k < nvalid) b[k] = (uint8_t)(word >> (8 * k));
                 }
-            } else if (MODE == L3_MODE_CHW) {
+            }
+        } else {
+            /* tensor mode: window test, optional mirror, table of the 256 normalised values */
+            const int32_t row = (int32_t)y - d.crop_y0;
+            if (row >= 0 && row < (int32_t)crop_h) {
+                global_u16* out16 = reinterpret_cast<global_u16*>((uintptr_t)d.out);
 #pragma unroll
-                for (int c = 0; c < 3; ++c) {
-                    const uint32_t word = c == 0 ? o0 : (c == 1 ? o1 : o2);
-                    uint8_t* dst = d.out + (size_t)c * d.plane_stride + (size_t)y * d.row_stride + x0 + xpix;
-                    if (nvalid == PPL) {
-                        *reinterpret_cast<global_u32_any*>((uintptr_t)dst) = word;
-                    } else if (nvalid) {
-                        global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
+                for (int k = 0; k < PPL; ++k) {
+                    int32_t col = (int32_t)(x0 + xpix + k) - d.crop_x0;
+                    if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
+                        if (d.flip) col = (int32_t)crop_w - 1 - col;
 #pragma unroll
-                        for (int k = 0; k < 3; ++k)
-                            if ((uint32_t)k < nvalid) b[k] = (uint8_t)(word >> (8 * k));
-                    }
-                }
-            } else {
-                /* tensor mode: window test, optional mirror, table of the 256 normalised values */
-                const int32_t row = (int32_t)y - d.crop_y0;
-                if (row >= 0 && row < (int32_t)crop_h) {
-                    global_u16* out16 = reinterpret_cast<global_u16*>((uintptr_t)d.out);
-#pragma unroll
-                    for (int k = 0; k < PPL; ++k) {
-                        int32_t col = (int32_t)(x0 + xpix + k) - d.crop_x0;
-                        if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
-                            if (d.flip) col = (int32_t)crop_w - 1 - col;
-#pragma unroll
-                            for (int c = 0; c < 3; ++c) {
-                                const uint32_t word = c == 0 ? o0 : (c == 1 ? o1 : o2);
-                                out16[((size_t)c * crop_h + row) * crop_w + col] =
-                                    s_lut[c * 256 + ((word >> (8 * k)) & 0xFFu)];
-                            }
+                        for (int ch = 0; ch < 3; ++ch) {
+                            const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
+                            out16[((size_t)ch * crop_h + row) * crop_w + col] =
+                                s_lut[ch * 256 + ((word >> (8 * k)) & 0xFFu)];
                         }
                     }
                 }
@@ -338,122 +329,127 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void l3_decode_kernel(
         }
     };
 
-    uint32_t prev[3][NP];
-#pragma unroll
-    for (int c = 0; c < 3; ++c) {
-#pragma unroll
-        for (int j = 0; j < NP; ++j) prev[c][j] = 0;   /* an all-zero row above predicts 0: row 0 is raw */
-        open_row(c, ring_fetch(ring_where<RING>(ring[c], bitpos[c])));
-    }
+    uint32_t prev0 = 0, prev1 = 0;   /* an all-zero row above predicts 0: row 0 is raw */
+    open_row(ring_fetch(ring_where<RING>(ring, bitpos)));
 
-    for (uint32_t r = 0; r < ph; ++r) {
-        const uint32_t slot = r % P;
-
-        if (slot == P - 1 && r + 1 < ph) {
-            /* top the rings up for rows r+1 .. r+P; bitpos[] is the record of row r+1 */
-#pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                const uint32_t need = (bitpos[c] >> 3) + G::AHEAD;
-                if (fill[c] < need) {
-#pragma unroll
-                    for (int t = 0; t < GPL; ++t) {
-                        const uint32_t idx = (fill[c] + (t * LPT + xl) * 16) & (RING - 1);
-                        *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring[c]) + idx) = pf[c][t];
-                        if (t == 0 && idx == 0)
-                            *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring[c]) + RING) = pf[c][t];
-                    }
-                    fill[c] += CHUNK;
-#ifndef L3_EXP_NO_REFILL_LOAD
-#pragma unroll
-                    for (int t = 0; t < GPL; ++t)
-                        pf[c][t] = load_granule(gaddr[c] + fill[c] + t * LPT * 16, file_end16);
-#endif
-                }
-            }
-            wave_lds_fence();
-        }
-        if (slot == 0 && r > 0) flush(r - P, P);
-
-        /* From here to the end of the iteration there is no branch.  The deltas of
-         * row r and the record of row r+1 travel from LDS while part 1 is computed;
-         * after the last row the record read does not exist, which is harmless. */
-        RingWords hdr_next[3], xw[3];
-#pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            xw[c] = ring_fetch(xwhere[c]);
-            hdr_next[c] = ring_fetch(hwhere[c]);
-        }
+    /* One row: no branch inside.  The deltas of the row and the record of the next
+     * row travel from LDS while part 1 is computed; after the last row the record
+     * read does not exist, which is harmless.  `park` is where this wave parks the
+     * row (one word p0 p1 p2 p3). */
+    auto do_row = [&](uint32_t* park) {
+        const RingWords xw = ring_fetch(xwhere);
+        const RingWords hdr_next = ring_fetch(hwhere);
         __builtin_amdgcn_sched_barrier(0);
 
         /* inverse filter, part 1: the prediction depends only on the row above
          * (registers + lane neighbours) */
-        uint32_t pred[3][NP];
-#pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            const uint32_t from_left = dpp_from_lower_lane(prev[c][NP - 1]);
-            const uint32_t from_right = dpp_from_upper_lane(prev[c][0]);
-#pragma unroll
-            for (int j = 0; j < NP; ++j) {
-                const uint32_t T = prev[c][j];
-                const uint32_t TL = __builtin_amdgcn_alignbit(T, j > 0 ? prev[c][j - 1] : from_left, 16);
-                const uint32_t TR =
-                    __builtin_amdgcn_alignbit(j < NP - 1 ? prev[c][j + 1] : from_right, T, 16);
-                pred[c][j] = predict2(TL, TR, T, border[j]);
-            }
-        }
-
+        const uint32_t from_left = dpp_from_lower_lane(prev1);
+        const uint32_t from_right = dpp_from_upper_lane(prev0);
+        const uint32_t mid = __builtin_amdgcn_alignbit(prev1, prev0, 16);   /* pixels 1,2 */
+        const uint32_t pred0 =
+            predict2(__builtin_amdgcn_alignbit(prev0, from_left, 16), mid, prev0, border[0]);
+        const uint32_t pred1 =
+            predict2(mid, __builtin_amdgcn_alignbit(from_right, prev1, 16), prev1, border[1]);
         __builtin_amdgcn_sched_barrier(0);
+
         /* base-delta: value = base + delta; part 2 of the filter: pixel = prediction
          * + value (both mod 256, one mask at the end) */
-#pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            wmax = max(wmax, w[c]);
-            const uint32_t x = ring_align(xw[c], xbit[c]);
-            const uint32_t d0 = x & mask[c];
-            const uint32_t d1 = __builtin_amdgcn_ubfe(x, w[c], w[c]);
-            const uint32_t d2 = __builtin_amdgcn_ubfe(x, w2[c], w[c]);
-            const uint32_t d3 = __builtin_amdgcn_ubfe(x, w3[c], w[c]);
-            prev[c][0] = (pred[c][0] + (d0 | (d1 << 16)) + base2[c]) & 0x00FF00FFu;
-            prev[c][1] = (pred[c][1] + (d2 | (d3 << 16)) + base2[c]) & 0x00FF00FFu;
-        }
+        wmax = max(wmax, w);
+        const uint32_t x = ring_align(xw, xbit);
+        const uint32_t d0 = __builtin_amdgcn_ubfe(x, 0, w);
+        const uint32_t d1 = __builtin_amdgcn_ubfe(x, w, w);
+        const uint32_t d2 = __builtin_amdgcn_ubfe(x, w2, w);
+        const uint32_t d3 = __builtin_amdgcn_ubfe(x, w3, w);
+        prev0 = (pred0 + (d0 | (d1 << 16)) + base2) & 0x00FF00FFu;
+        prev1 = (pred1 + (d2 | (d3 << 16)) + base2) & 0x00FF00FFu;
+        *park = __builtin_amdgcn_perm(prev1, prev0, 0x06040200u);
 
-        /* park the row: bytes in output order */
-        uint32_t o0, o1, o2;
-        if (MODE == L3_MODE_HWC) {
-            /* R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3 */
-            const uint32_t t0 = __builtin_amdgcn_perm(prev[1][0], prev[0][0], 0x020c0400u);
-            o0 = __builtin_amdgcn_perm(prev[2][0], t0, 0x03040100u);
-            const uint32_t t1 = __builtin_amdgcn_perm(prev[2][0], prev[1][0], 0x0c0c0602u);
-            const uint32_t t2 = __builtin_amdgcn_perm(prev[1][1], prev[0][1], 0x04000c0cu);
-            o1 = t1 | t2;
-            const uint32_t t3 = __builtin_amdgcn_perm(prev[0][1], prev[2][1], 0x020c0600u);
-            o2 = __builtin_amdgcn_perm(prev[1][1], t3, 0x03060100u);
-        } else {
-            /* one word per channel: p0 p1 p2 p3 */
-            o0 = __builtin_amdgcn_perm(prev[0][1], prev[0][0], 0x06040200u);
-            o1 = __builtin_amdgcn_perm(prev[1][1], prev[1][0], 0x06040200u);
-            o2 = __builtin_amdgcn_perm(prev[2][1], prev[2][0], 0x06040200u);
-        }
-        park[(slot * 3 + 0) * 64] = o0;
-        park[(slot * 3 + 1) * 64] = o1;
-        park[(slot * 3 + 2) * 64] = o2;
-
-        /* open row r+1 */
         __builtin_amdgcn_sched_barrier(0);
+        open_row(hdr_next);
+    };
+
+    /* Periods of P = 3 rows, unrolled so that the row's place in the period is a
+     * constant: the previous period is written out before row 0, the ring is topped
+     * up before row 2.  Only the last period can be shorter. */
+    /* Waves that are ahead yield to waves that are behind (the hardware otherwise
+     * favours the oldest wave, and the youngest ones would finish the kernel alone):
+     * the wave's issue priority drops by one in each quarter of its rows. */
+    const uint32_t quarter = (ph + 3) / 4;
+    uint32_t next_drop = quarter, stage = 0;
+    __builtin_amdgcn_s_setprio(3);
+
+    uint32_t buf = 0;
+    for (uint32_t r = 0; r < ph; r += P) {
+        const uint32_t rows = min((uint32_t)P, ph - r);
+        if (r >= next_drop) {
+            next_drop += quarter;
+            ++stage;
+            if (stage == 1) __builtin_amdgcn_s_setprio(2);
+            else if (stage == 2) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
+        if (r > 0) {
+            /* all three channels of the previous period are parked: write them out */
+            __syncthreads();
+            flush(buf ^ 1u, r - P, P);
+        }
+        uint32_t* park = &parked[buf][0][c][lane];
+        do_row(park);
+        if (rows > 1) do_row(park + 3 * 64);
+        if (rows > 2) {
+            if (r + P < ph) {
+                /* top the ring up for rows r+3 .. r+5; bitpos is the record of row r+3 */
+                const uint32_t need = (bitpos >> 3) + G::AHEAD;
+                if (fill < need) {
 #pragma unroll
-        for (int c = 0; c < 3; ++c) open_row(c, hdr_next[c]);
+                    for (int t = 0; t < GPL; ++t) {
+                        const uint32_t idx = (fill + (t * LPT + xl) * 16) & (RING - 1);
+                        *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + idx) = pf[t];
+                        if (t == 0 && idx == 0)
+                            *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + RING) = pf[t];
+                    }
+                    fill += CHUNK;
+#pragma unroll
+                    for (int t = 0; t < GPL; ++t)
+                        pf[t] = load_granule(gaddr + fill + t * LPT * 16, file_end16);
+                }
+                wave_lds_fence();
+            }
+            do_row(park + 2 * 3 * 64);
+        }
+        buf ^= 1u;
     }
     {
         const uint32_t first = ((ph - 1) / P) * P;
-        flush(first, ph - first);
+        __syncthreads();
+        flush(buf ^ 1u, first, ph - first);
     }
 
     if (wmax > 8) flags |= L3_STATUS_BAD_WIDTH;
-    /* bitpos[] is one (non-existent) row past the end: step back over it */
-#pragma unroll
-    for (int c = 0; c < 3; ++c)
-        if (bitpos[c] - 12 - pw * w[c] > endbit[c]) flags |= L3_STATUS_OVERRUN;
+    /* bitpos is one (non-existent) row past the end: step back over it */
+    if (bitpos - 12 - pw * w > endbit) flags |= L3_STATUS_OVERRUN;
     if (flags && active && status) atomicOr(&status[d.status_index], flags);
+}
+
+/* Descriptors in a device table (any batch size)... */
+template <int N, int MODE>
+__global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel(
+    const L3ImageDesc* __restrict__ descs, uint32_t* __restrict__ status, uint32_t crop_w,
+    uint32_t crop_h, const uint16_t* __restrict__ lut) {
+    decode_unit<N, MODE>(descs[blockIdx.y], status, crop_w, crop_h, lut);
+}
+
+/* ...or, for small batches, inside the kernel arguments: no upload, no dependency
+ * on a copy, so consecutive calls run back to back. */
+constexpr int kArgDescs = 32;
+struct DescPack { L3ImageDesc d[kArgDescs]; };
+static_assert(sizeof(DescPack) + 64 <= 4096, "kernel argument segment");
+
+template <int N, int MODE>
+__global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel_args(
+    const DescPack pack, uint32_t* __restrict__ status, uint32_t crop_w, uint32_t crop_h,
+    const uint16_t* __restrict__ lut) {
+    decode_unit<N, MODE>(pack.d[blockIdx.y], status, crop_w, crop_h, lut);
 }
 
 /* y = (x/255 - mean) / stdv for all 256 byte values of each channel, IEEE
@@ -502,6 +498,23 @@ decode_kernel_t kernel_for_mode(int mode) {
     }
 }
 
+typedef void (*decode_kernel_args_t)(const DescPack, uint32_t*, uint32_t, uint32_t, const uint16_t*);
+
+template <int N>
+decode_kernel_args_t kernel_args_for_mode(int mode) {
+    switch (mode) {
+        case L3_MODE_HWC: return l3_decode_kernel_args<N, L3_MODE_HWC>;
+        case L3_MODE_CHW: return l3_decode_kernel_args<N, L3_MODE_CHW>;
+        default: return l3_decode_kernel_args<N, L3_MODE_TENSOR>;
+    }
+}
+
+decode_kernel_args_t pick_kernel_args(int n, int mode) {
+    if (n == 32) return kernel_args_for_mode<32>(mode);
+    if (n == 64) return kernel_args_for_mode<64>(mode);
+    return kernel_args_for_mode<128>(mode);
+}
+
 decode_kernel_t pick_kernel(int n, int mode, int* tiles_per_wave) {
     if (n == 32) { *tiles_per_wave = Geom<32>::TPW; return kernel_for_mode<32>(mode); }
     if (n == 64) { *tiles_per_wave = Geom<64>::TPW; return kernel_for_mode<64>(mode); }
@@ -512,6 +525,8 @@ decode_kernel_t pick_kernel(int n, int mode, int* tiles_per_wave) {
 
 struct l3_ctx {
     int device = 0;
+    L3ImageDesc* scratch = nullptr;       /* host: descriptors of the call being planned */
+    size_t scratch_cap = 0;
     size_t cap = 0;                       /* descriptors per slot */
     L3ImageDesc* h_stage[kSlots] = {};    /* pinned host */
     L3ImageDesc* d_descs[kSlots] = {};    /* device */
@@ -602,15 +617,16 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return L3_ERR_DEVICE;
-    l3_status st = ensure_capacity(ctx, (size_t)n);
-    if (st != L3_OK) return st;
-
-    const int slot = ctx->next;
-    if (ctx->pending[slot]) {
-        if (hipEventSynchronize(ctx->done[slot]) != hipSuccess) return L3_ERR_DEVICE;
-        ctx->pending[slot] = false;
+    l3_status st = L3_OK;
+    if ((size_t)n > ctx->scratch_cap) {
+        size_t cap = 256;
+        while (cap < (size_t)n) cap *= 2;
+        L3ImageDesc* grown = static_cast<L3ImageDesc*>(std::realloc(ctx->scratch, cap * sizeof(L3ImageDesc)));
+        if (!grown) return L3_ERR_DEVICE;
+        ctx->scratch = grown;
+        ctx->scratch_cap = cap;
     }
-    L3ImageDesc* stage = ctx->h_stage[slot];
+    L3ImageDesc* stage = ctx->scratch;
 
     /* descriptors grouped by patch size: classes 32, 64, 128 in this order */
     static const int kClasses[3] = {32, 64, 128};
@@ -670,12 +686,32 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     }
     class_begin[3] = filled;
 
-    L3ImageDesc* d_descs = ctx->d_descs[slot];
-    if (hipMemcpyAsync(d_descs, stage, (size_t)n * sizeof(L3ImageDesc), hipMemcpyHostToDevice,
-                       ctx->copy_stream) != hipSuccess ||
-        hipEventRecord(ctx->copied[slot], ctx->copy_stream) != hipSuccess ||
-        hipStreamWaitEvent(stream, ctx->copied[slot], 0) != hipSuccess)
-        return L3_ERR_DEVICE;
+    /* Small batches travel inside the kernel arguments; larger ones through a device
+     * table that is uploaded on the context's own stream. */
+    bool in_args = true;
+    for (int k = 0; k < 3; ++k)
+        if (class_begin[k + 1] - class_begin[k] > kArgDescs) in_args = false;
+
+    int slot = -1;
+    L3ImageDesc* d_descs = nullptr;
+    if (!in_args || mode == L3_MODE_TENSOR) {
+        st = ensure_capacity(ctx, (size_t)n);
+        if (st != L3_OK) return st;
+        slot = ctx->next;
+        if (ctx->pending[slot]) {
+            if (hipEventSynchronize(ctx->done[slot]) != hipSuccess) return L3_ERR_DEVICE;
+            ctx->pending[slot] = false;
+        }
+    }
+    if (!in_args) {
+        std::memcpy(ctx->h_stage[slot], stage, (size_t)n * sizeof(L3ImageDesc));
+        d_descs = ctx->d_descs[slot];
+        if (hipMemcpyAsync(d_descs, ctx->h_stage[slot], (size_t)n * sizeof(L3ImageDesc),
+                           hipMemcpyHostToDevice, ctx->copy_stream) != hipSuccess ||
+            hipEventRecord(ctx->copied[slot], ctx->copy_stream) != hipSuccess ||
+            hipStreamWaitEvent(stream, ctx->copied[slot], 0) != hipSuccess)
+            return L3_ERR_DEVICE;
+    }
     if (d_status)
         hipLaunchKernelGGL(l3_fill_u32_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, d_status,
                            (uint32_t)n, 0u);
@@ -688,19 +724,28 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     for (int k = 0; k < 3; ++k) {
         const int count = class_begin[k + 1] - class_begin[k];
         if (count == 0 || max_units[k] == 0) continue;
+        const uint32_t gx = max_units[k];
+        if (in_args) {
+            DescPack pack;
+            std::memcpy(pack.d, stage + class_begin[k], (size_t)count * sizeof(L3ImageDesc));
+            hipLaunchKernelGGL(pick_kernel_args(kClasses[k], mode), dim3(gx, (uint32_t)count),
+                               dim3(kBlockThreads), 0, stream, pack, d_status, crop_w, crop_h, table);
+            continue;
+        }
         int tpw = 1;
         decode_kernel_t kern = pick_kernel(kClasses[k], mode, &tpw);
-        const uint32_t gx = (max_units[k] + kWavesPerBlock - 1) / kWavesPerBlock;
         for (int first = 0; first < count; first += 65535) {
             const int m = count - first < 65535 ? count - first : 65535;
-            hipLaunchKernelGGL(kern, dim3(gx, (uint32_t)m), dim3(64 * kWavesPerBlock), 0, stream,
+            hipLaunchKernelGGL(kern, dim3(gx, (uint32_t)m), dim3(kBlockThreads), 0, stream,
                                d_descs + class_begin[k] + first, d_status, crop_w, crop_h, table);
         }
     }
     if (hipGetLastError() != hipSuccess) return L3_ERR_DEVICE;
-    if (hipEventRecord(ctx->done[slot], stream) != hipSuccess) return L3_ERR_DEVICE;
-    ctx->pending[slot] = true;
-    ctx->next = (slot + 1) % kSlots;
+    if (slot >= 0) {
+        if (hipEventRecord(ctx->done[slot], stream) != hipSuccess) return L3_ERR_DEVICE;
+        ctx->pending[slot] = true;
+        ctx->next = (slot + 1) % kSlots;
+    }
     return L3_OK;
 }
 
@@ -750,6 +795,7 @@ void l3_ctx_destroy(l3_ctx* ctx) {
         (void)hipStreamDestroy(ctx->copy_stream);
     }
     release_slots(ctx);
+    std::free(ctx->scratch);
     delete ctx;
 }
 
