@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--workload", default="cityscapes")
     ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="after the timed steps also run 5 plain device copies of BYTES bytes "
+                         "(a kernel of known traffic, to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (decode needs no exchange between "
@@ -99,6 +102,13 @@ def main():
         for t, im in zip(sets[s][1], images):
             if not np.array_equal(t.cpu().numpy().reshape(im.shape), im):
                 raise SystemExit("bench.py: decoded output differs from the input images")
+
+    if args.copy_calibration:
+        src = torch.ones(args.copy_calibration, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     ms_per_step = wall * 1e3 / args.steps
     launch_ms = gpu_ms / args.steps

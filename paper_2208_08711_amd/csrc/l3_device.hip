@@ -94,46 +94,70 @@ __device__ __forceinline__ uint32_t pk_mad_i16(uint32_t a, uint32_t b, uint32_t 
     return d;
 }
 
-/* Section 4.2, custom Paeth filter, on two pixels at once (16-bit fields holding
- * 0..255).  Value-wise the nearest of TL, TR, T to TL + TR - T is: with
- * lo = min(TL,TR), hi = max(TL,TR), dl = T - lo, dh = hi - T (signed):
- * lo if dl >= 2*dh, else hi if dh >= 2*dl, else T.  The stated tie order
- * (TL, TR, T) only ever chooses between equal values, except T against a
- * neighbour, where the neighbour wins: that is the ">=" above.
+/* Section 4.2, custom Paeth filter, on 2 x 2 pixels at once (two registers of
+ * two 16-bit fields holding 0..255).  Value-wise the nearest of TL, TR, T to
+ * TL + TR - T is: with lo = min(TL,TR), hi = max(TL,TR), dl = T - lo,
+ * dh = hi - T (signed): lo if dl >= 2*dh, else hi if dh >= 2*dl, else T.  The
+ * stated tie order (TL, TR, T) only ever chooses between equal values, except T
+ * against a neighbour, where the neighbour wins: that is the ">=" above.
  * `border` has all ones in the fields whose pixel sits in the first or last
- * column of its patch, where the prediction is T. */
-__device__ __forceinline__ uint32_t predict2(uint32_t TL, uint32_t TR, uint32_t T, uint32_t border) {
-    const u16x2 a = __builtin_bit_cast(u16x2, TL), b = __builtin_bit_cast(u16x2, TR),
-                c = __builtin_bit_cast(u16x2, T);
-    const u16x2 lo = __builtin_elementwise_min(a, b), hi = __builtin_elementwise_max(a, b);
-    const uint32_t dl = __builtin_bit_cast(uint32_t, (u16x2)(c - lo));
-    const uint32_t dh = __builtin_bit_cast(uint32_t, (u16x2)(hi - c));
+ * column of its patch, where the prediction is T.  The two registers are
+ * worked on in lockstep so that dependent packed instructions are not adjacent. */
+struct Pred2 { uint32_t p0, p1; };
+__device__ __forceinline__ Pred2 predict4(uint32_t TL0, uint32_t TR0, uint32_t T0, uint32_t border0,
+                                          uint32_t TL1, uint32_t TR1, uint32_t T1, uint32_t border1) {
+    const u16x2 a0 = __builtin_bit_cast(u16x2, TL0), b0 = __builtin_bit_cast(u16x2, TR0),
+                c0 = __builtin_bit_cast(u16x2, T0);
+    const u16x2 a1 = __builtin_bit_cast(u16x2, TL1), b1 = __builtin_bit_cast(u16x2, TR1),
+                c1 = __builtin_bit_cast(u16x2, T1);
+    const u16x2 lo0 = __builtin_elementwise_min(a0, b0), lo1 = __builtin_elementwise_min(a1, b1);
+    const u16x2 hi0 = __builtin_elementwise_max(a0, b0), hi1 = __builtin_elementwise_max(a1, b1);
+    const uint32_t dl0 = __builtin_bit_cast(uint32_t, (u16x2)(c0 - lo0));
+    const uint32_t dl1 = __builtin_bit_cast(uint32_t, (u16x2)(c1 - lo1));
+    const uint32_t dh0 = __builtin_bit_cast(uint32_t, (u16x2)(hi0 - c0));
+    const uint32_t dh1 = __builtin_bit_cast(uint32_t, (u16x2)(hi1 - c1));
     const uint32_t minus2 = 0xFFFEFFFEu;
-    const s16x2 t_lo = __builtin_bit_cast(s16x2, pk_mad_i16(dh, minus2, dl));   /* dl - 2 dh */
-    const s16x2 t_hi = __builtin_bit_cast(s16x2, pk_mad_i16(dl, minus2, dh));   /* dh - 2 dl */
-    uint32_t not_lo = __builtin_bit_cast(uint32_t, (s16x2)(t_lo >> 15));
-    uint32_t not_hi = __builtin_bit_cast(uint32_t, (s16x2)(t_hi >> 15));
-    asm("" : "+v"(not_lo));   /* keep the masks packed: no per-half compare/select */
-    asm("" : "+v"(not_hi));
-    const uint32_t H = __builtin_bit_cast(uint32_t, hi), L = __builtin_bit_cast(uint32_t, lo);
-    const uint32_t r = (not_hi & T) | (~not_hi & H);
-    const uint32_t p = (not_lo & r) | (~not_lo & L);
-    return (border & T) | (~border & p);
+    const s16x2 tl0 = __builtin_bit_cast(s16x2, pk_mad_i16(dh0, minus2, dl0));   /* dl - 2 dh */
+    const s16x2 tl1 = __builtin_bit_cast(s16x2, pk_mad_i16(dh1, minus2, dl1));
+    const s16x2 th0 = __builtin_bit_cast(s16x2, pk_mad_i16(dl0, minus2, dh0));   /* dh - 2 dl */
+    const s16x2 th1 = __builtin_bit_cast(s16x2, pk_mad_i16(dl1, minus2, dh1));
+    uint32_t not_lo0 = __builtin_bit_cast(uint32_t, (s16x2)(tl0 >> 15));
+    uint32_t not_lo1 = __builtin_bit_cast(uint32_t, (s16x2)(tl1 >> 15));
+    uint32_t not_hi0 = __builtin_bit_cast(uint32_t, (s16x2)(th0 >> 15));
+    uint32_t not_hi1 = __builtin_bit_cast(uint32_t, (s16x2)(th1 >> 15));
+    asm("" : "+v"(not_lo0), "+v"(not_lo1), "+v"(not_hi0), "+v"(not_hi1));   /* keep the masks packed */
+    const uint32_t H0 = __builtin_bit_cast(uint32_t, hi0), L0 = __builtin_bit_cast(uint32_t, lo0);
+    const uint32_t H1 = __builtin_bit_cast(uint32_t, hi1), L1 = __builtin_bit_cast(uint32_t, lo1);
+    /* bitop3 0xCA: first ? second : third */
+    const uint32_t r0 = __builtin_amdgcn_bitop3_b32(not_hi0, T0, H0, 0xCA);
+    const uint32_t r1 = __builtin_amdgcn_bitop3_b32(not_hi1, T1, H1, 0xCA);
+    const uint32_t q0 = __builtin_amdgcn_bitop3_b32(not_lo0, r0, L0, 0xCA);
+    const uint32_t q1 = __builtin_amdgcn_bitop3_b32(not_lo1, r1, L1, 0xCA);
+    Pred2 out;
+    out.p0 = __builtin_amdgcn_bitop3_b32(border0, T0, q0, 0xCA);
+    out.p1 = __builtin_amdgcn_bitop3_b32(border1, T1, q1, 0xCA);
+    return out;
 }
 
 /* The 32 stream bits starting at bit `bit` of a ring live in two aligned words
  * (bit counts from the ring's aligned origin; the ring holds the stream modulo
  * RING bytes).  Three steps, so that the LDS address can be computed one row
- * ahead and the read issued long before its result is needed. */
+ * ahead and the read issued long before its result is needed.  Rings are
+ * addressed by their 32-bit LDS byte address. */
+typedef __attribute__((address_space(3))) const uint32_t lds_const_u32;
 struct RingWords { uint32_t lo, hi; };
 template <int RING>
-__device__ __forceinline__ const uint32_t* ring_where(const uint32_t* ring, uint32_t bit) {
-    return ring + ((bit >> 5) & (RING / 4 - 1));
+__device__ __forceinline__ uint32_t ring_where(uint32_t ring_lds, uint32_t bit) {
+    static_assert((RING & (RING - 1)) == 0, "ring size is a power of two");
+    uint32_t word = __builtin_amdgcn_ubfe(bit, 5, __builtin_ctz(RING / 4));
+    asm("" : "+v"(word));            /* keep bfe + shift-add: two instructions, not three */
+    return (word << 2) + ring_lds;
 }
-__device__ __forceinline__ RingWords ring_fetch(const uint32_t* where) {
+__device__ __forceinline__ RingWords ring_fetch(uint32_t where) {
+    lds_const_u32* p = reinterpret_cast<lds_const_u32*>(where);
     RingWords v;
-    v.lo = where[0];
-    v.hi = where[1];   /* may be the mirror word behind the ring */
+    v.lo = p[0];
+    v.hi = p[1];   /* may be the mirror word behind the ring */
     return v;
 }
 __device__ __forceinline__ uint32_t ring_align(RingWords v, uint32_t bit) {
@@ -243,8 +267,9 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
 
     /* what the arithmetic of a row needs from its base-delta record */
     uint32_t w, w2, w3, base2, xbit, wmax = 0;
-    const uint32_t* xwhere;   /* LDS words holding this lane's deltas of the open row */
-    const uint32_t* hwhere;   /* LDS words holding the record after the open row */
+    uint32_t xwhere;   /* LDS address of the words holding this lane's deltas of the open row */
+    uint32_t hwhere;   /* LDS address of the words holding the record after the open row */
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)ring;
 
     /* Opens the row whose record (4-bit width, 8-bit base) is at bitpos: works out
      * where this lane's 4 deltas are (4w <= 32 contiguous bits) and advances bitpos
@@ -258,8 +283,8 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
         const uint32_t dbit = bitpos + 12;
         bitpos = dbit + pw * wr;
         xbit = dbit + xpix * wr;
-        xwhere = ring_where<RING>(ring, xbit);
-        hwhere = ring_where<RING>(ring, bitpos);
+        xwhere = ring_where<RING>(ring_lds, xbit);
+        hwhere = ring_where<RING>(ring_lds, bitpos);
         w = wr;
         w2 = wr + wr;
         w3 = w2 + wr;
@@ -330,7 +355,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
     };
 
     uint32_t prev0 = 0, prev1 = 0;   /* an all-zero row above predicts 0: row 0 is raw */
-    open_row(ring_fetch(ring_where<RING>(ring, bitpos)));
+    open_row(ring_fetch(ring_where<RING>(ring_lds, bitpos)));
 
     /* One row: no branch inside.  The deltas of the row and the record of the next
      * row travel from LDS while part 1 is computed; after the last row the record
@@ -346,10 +371,9 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
         const uint32_t from_left = dpp_from_lower_lane(prev1);
         const uint32_t from_right = dpp_from_upper_lane(prev0);
         const uint32_t mid = __builtin_amdgcn_alignbit(prev1, prev0, 16);   /* pixels 1,2 */
-        const uint32_t pred0 =
-            predict2(__builtin_amdgcn_alignbit(prev0, from_left, 16), mid, prev0, border[0]);
-        const uint32_t pred1 =
-            predict2(mid, __builtin_amdgcn_alignbit(from_right, prev1, 16), prev1, border[1]);
+        const Pred2 pr = predict4(__builtin_amdgcn_alignbit(prev0, from_left, 16), mid, prev0, border[0],
+                                  mid, __builtin_amdgcn_alignbit(from_right, prev1, 16), prev1, border[1]);
+        const uint32_t pred0 = pr.p0, pred1 = pr.p1;
         __builtin_amdgcn_sched_barrier(0);
 
         /* base-delta: value = base + delta; part 2 of the filter: pixel = prediction
