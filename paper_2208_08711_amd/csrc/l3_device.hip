@@ -256,10 +256,14 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
 
     /* per-lane constants of the row loop */
     const uint32_t xpix = xl * PPL;                         /* first pixel column of this lane */
+    /* The lane's 4 pixels sit in two registers of two 16-bit fields: register 0 holds
+     * pixels (0, 2), register 1 pixels (1, 3).  Then the top-right neighbours of
+     * register 0 are register 1 itself and the top-left neighbours of register 1 are
+     * register 0; only the two outer neighbours need a lane shift. */
     uint32_t border[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        const uint32_t xa = xpix + 2 * j, xb = xa + 1;
+        const uint32_t xa = xpix + j, xb = xa + 2;
         border[j] = ((xa == 0 || xa + 1 == pw) ? 0x0000FFFFu : 0u) |
                     ((xb == 0 || xb + 1 == pw) ? 0xFFFF0000u : 0u);
     }
@@ -368,11 +372,12 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
 
         /* inverse filter, part 1: the prediction depends only on the row above
          * (registers + lane neighbours) */
-        const uint32_t from_left = dpp_from_lower_lane(prev1);
-        const uint32_t from_right = dpp_from_upper_lane(prev0);
-        const uint32_t mid = __builtin_amdgcn_alignbit(prev1, prev0, 16);   /* pixels 1,2 */
-        const Pred2 pr = predict4(__builtin_amdgcn_alignbit(prev0, from_left, 16), mid, prev0, border[0],
-                                  mid, __builtin_amdgcn_alignbit(from_right, prev1, 16), prev1, border[1]);
+        const uint32_t from_left = dpp_from_lower_lane(prev1);    /* pixels (1,3) of the lane below */
+        const uint32_t from_right = dpp_from_upper_lane(prev0);   /* pixels (0,2) of the lane above */
+        /* pixels (0,2): top-left = (3 of the lower lane, 1), top-right = (1,3);
+         * pixels (1,3): top-left = (0,2), top-right = (2, 0 of the upper lane) */
+        const Pred2 pr = predict4(__builtin_amdgcn_alignbit(prev1, from_left, 16), prev1, prev0, border[0],
+                                  prev0, __builtin_amdgcn_alignbit(from_right, prev0, 16), prev1, border[1]);
         const uint32_t pred0 = pr.p0, pred1 = pr.p1;
         __builtin_amdgcn_sched_barrier(0);
 
@@ -384,9 +389,9 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
         const uint32_t d1 = __builtin_amdgcn_ubfe(x, w, w);
         const uint32_t d2 = __builtin_amdgcn_ubfe(x, w2, w);
         const uint32_t d3 = __builtin_amdgcn_ubfe(x, w3, w);
-        prev0 = (pred0 + (d0 | (d1 << 16)) + base2) & 0x00FF00FFu;
-        prev1 = (pred1 + (d2 | (d3 << 16)) + base2) & 0x00FF00FFu;
-        *park = __builtin_amdgcn_perm(prev1, prev0, 0x06040200u);
+        prev0 = (pred0 + (d0 | (d2 << 16)) + base2) & 0x00FF00FFu;
+        prev1 = (pred1 + (d1 | (d3 << 16)) + base2) & 0x00FF00FFu;
+        *park = __builtin_amdgcn_perm(prev1, prev0, 0x06020400u);   /* p0 p1 p2 p3 */
 
         __builtin_amdgcn_sched_barrier(0);
         open_row(hdr_next);
