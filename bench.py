@@ -57,6 +57,9 @@ def make_workload(name):
         return synth.config3(32), "Cityscapes-shaped: 32 RGB images 2048x1024, Voronoi regions + texture, N=128"
     if name == "imagenet":
         return synth.config2(256), "ImageNet-shaped: 256 RGB images 400-500 x 300-375, cosine field + noise, N=32"
+    if name == "train224":
+        return synth.config2(256), ("Fused training-input path: the ImageNet-shaped batch of 256, seeded 224x224 "
+                                    "window + mirror + per-channel normalise to bf16 NCHW, N=32")
     if name == "uhd":
         return synth.config4(8), "UHD stress: 8 RGB images 3840x2160, half compressible, half random, N=128"
     raise SystemExit(f"unknown workload {name}")
@@ -96,33 +99,62 @@ def main():
 
     ctx = l3.Context(0)
     infos = [l3.peek_header(f) for f in files]
+    fused = args.workload == "train224"
     sets = []
-    for s in range(args.sets):
-        dfiles = [torch.from_numpy(np.frombuffer(f, dtype=np.uint8).copy()).cuda() for f in files]
-        outs = [torch.empty((im.shape[0], im.shape[1] * 3), dtype=torch.uint8, device="cuda")
-                for im in images]
-        sets.append((l3.PreparedBatch(dfiles, infos, outs), outs))
+    if fused:
+        from paper_2208_08711_amd import synth
+        crops = synth.config5_crops([(im.shape[1], im.shape[0]) for im in images])
+        for s in range(args.sets):
+            dfiles = [torch.from_numpy(np.frombuffer(f, dtype=np.uint8).copy()).cuda() for f in files]
+            out = torch.empty((n, 3, 224, 224), dtype=torch.bfloat16, device="cuda")
+            sets.append((l3.PreparedCropBatch(dfiles, infos, crops, synth.IMAGENET_MEAN,
+                                              synth.IMAGENET_STD), out))
+
+        def step(k):
+            batch, out = sets[k % args.sets]
+            l3.decode_crop_normalize_batch_prepared(ctx, batch, 224, 224, out, dtype=l3.BF16,
+                                                    stream=stream)
+    else:
+        for s in range(args.sets):
+            dfiles = [torch.from_numpy(np.frombuffer(f, dtype=np.uint8).copy()).cuda() for f in files]
+            outs = [torch.empty((im.shape[0], im.shape[1] * 3), dtype=torch.uint8, device="cuda")
+                    for im in images]
+            sets.append((l3.PreparedBatch(dfiles, infos, outs), outs))
+
+        def step(k):
+            l3.decode_batch_prepared(ctx, sets[k % args.sets][0], stream=stream)
 
     stream = torch.cuda.current_stream()
     for k in range(args.warmup):
-        l3.decode_batch_prepared(ctx, sets[k % args.sets][0], stream=stream)
+        step(k)
     torch.cuda.synchronize()
 
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record(stream)
     for k in range(args.steps):
-        l3.decode_batch_prepared(ctx, sets[k % args.sets][0], stream=stream)
+        step(k)
     ev1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     gpu_ms = ev0.elapsed_time(ev1)
 
-    # the result of the last steps must be the images
-    for s in range(args.sets):
-        for t, im in zip(sets[s][1], images):
-            if not np.array_equal(t.cpu().numpy().reshape(im.shape), im):
-                raise SystemExit("bench.py: decoded output differs from the input images")
+    # the result of the last steps must be what the oracle computes
+    if fused:
+        got = sets[0][1].view(torch.int16).cpu().numpy().view(np.uint16)
+        for i in (0, n // 2, n - 1):
+            x0, y0, flip = crops[i]
+            want = oracle.crop_normalize(images[i], x0, y0, flip, 224, 224, synth.IMAGENET_MEAN,
+                                         synth.IMAGENET_STD, 0)
+            if not np.array_equal(got[i], want):
+                raise SystemExit("bench.py: fused output differs from the oracle")
+        # bytes of this path: the 16-bit tensor written, the whole files counted as read
+        decoded_bytes = n * 3 * 224 * 224 * 2
+    else:
+        for s in range(args.sets):
+            for t, im in zip(sets[s][1], images):
+                if not np.array_equal(t.cpu().numpy().reshape(im.shape), im):
+                    raise SystemExit("bench.py: decoded output differs from the input images")
 
     if args.copy_calibration:
         src = torch.ones(args.copy_calibration, dtype=torch.uint8, device="cuda")
@@ -150,7 +182,7 @@ def main():
         "vs_baseline": None,
         "dtype": "u8",
         "data": "synthetic",
-        "config": {"workload": label, "batch": n, "layout": "HWC uint8",
+        "config": {"workload": label, "batch": n, "layout": "NCHW bf16" if fused else "HWC uint8",
                    "buffer_sets_rotated": args.sets,
                    "compressed_over_raw": round(file_bytes / decoded_bytes, 4)},
         "decoded_GBps": decoded_bytes / (ms_per_step * 1e-3) / 1e9,

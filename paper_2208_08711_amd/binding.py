@@ -229,3 +229,27 @@ def decode_crop_normalize_batch(ctx, files, infos, crops, crop_w, crop_h, mean, 
         ctx.handle, arr, cr, n, crop_w, crop_h, m, s, dtype, ctypes.c_void_p(out.data_ptr()),
         ctypes.c_void_p(status.data_ptr() if status is not None else None), _stream_ptr(stream)),
         "l3_decode_crop_normalize_batch")
+
+
+class PreparedCropBatch:
+    """Marshalled l3_item and l3_crop arrays for the fused call, reusable across calls."""
+
+    def __init__(self, files, infos, crops, mean, stdv):
+        self.n = len(files)
+        self.items = _items(files, infos, None, None)
+        self.crops = (_Crop * max(self.n, 1))()
+        for i, (x0, y0, flip) in enumerate(crops):
+            self.crops[i].x0, self.crops[i].y0, self.crops[i].flip = int(x0), int(y0), int(bool(flip))
+        self.mean = (ctypes.c_float * 3)(*mean)
+        self.stdv = (ctypes.c_float * 3)(*stdv)
+        self._keep = files
+
+
+def decode_crop_normalize_batch_prepared(ctx, batch, crop_w, crop_h, out, dtype=BF16, status=None,
+                                         stream=None):
+    """l3_decode_crop_normalize_batch on a PreparedCropBatch: no per-call marshalling."""
+    _check(_load().l3_decode_crop_normalize_batch(
+        ctx.handle, batch.items, batch.crops, batch.n, crop_w, crop_h, batch.mean, batch.stdv, dtype,
+        ctypes.c_void_p(out.data_ptr()),
+        ctypes.c_void_p(status.data_ptr() if status is not None else None), _stream_ptr(stream)),
+        "l3_decode_crop_normalize_batch")

@@ -49,11 +49,14 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
 typedef u32x3 u32x3_any __attribute__((aligned(1)));      /* any byte alignment */
 typedef uint32_t u32_any __attribute__((aligned(1)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef u32x2 u32x2_any __attribute__((aligned(1)));
 
 typedef __attribute__((address_space(1))) const u32x4 global_const_u32x4;
 typedef __attribute__((address_space(1))) const u32_any global_const_u32_any;
 typedef __attribute__((address_space(1))) u32x3_any global_u32x3_any;
 typedef __attribute__((address_space(1))) u32_any global_u32_any;
+typedef __attribute__((address_space(1))) u32x2_any global_u32x2_any;
 typedef __attribute__((address_space(1))) uint8_t global_u8;
 typedef __attribute__((address_space(1))) uint16_t global_u16;
 
@@ -212,7 +215,9 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
     const uint32_t tx = d.tile_x_first + (active ? txr : d.tile_x_count - 1);
     const uint32_t x0 = tx * N, y0 = ty * N;
     const uint32_t pw = min((uint32_t)N, d.width - x0);
-    const uint32_t ph = min((uint32_t)N, d.height - y0);     /* same for the whole workgroup */
+    uint32_t ph = min((uint32_t)N, d.height - y0);           /* same for the whole workgroup */
+    if (MODE == L3_MODE_TENSOR)                              /* rows below the window are not needed */
+        ph = min(ph, (uint32_t)d.crop_y0 + crop_h - y0);
     const uint32_t patches = d.tiles_x * d.tiles_y;
     const uint32_t data_len = (uint32_t)(d.file_len - d.header_bytes);
     const uint8_t* file_end16 =
@@ -337,20 +342,44 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                 }
             }
         } else {
-            /* tensor mode: window test, optional mirror, table of the 256 normalised values */
+            /* tensor mode: window test, optional mirror, table of the 256 normalised
+             * values.  A lane whose 4 pixels all lie inside the window writes 4 elements
+             * (8 bytes) per channel at once, mirrored or not; edge lanes go element by
+             * element. */
             const int32_t row = (int32_t)y - d.crop_y0;
-            if (row >= 0 && row < (int32_t)crop_h) {
-                global_u16* out16 = reinterpret_cast<global_u16*>((uintptr_t)d.out);
+            if (row >= 0 && row < (int32_t)crop_h && nvalid) {
+                const int32_t col0 = (int32_t)(x0 + xpix) - d.crop_x0;   /* window column of pixel 0 */
+                const bool whole = nvalid == PPL && col0 >= 0 && col0 + PPL <= (int32_t)crop_w;
 #pragma unroll
-                for (int k = 0; k < PPL; ++k) {
-                    int32_t col = (int32_t)(x0 + xpix + k) - d.crop_x0;
-                    if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
-                        if (d.flip) col = (int32_t)crop_w - 1 - col;
+                for (int ch = 0; ch < 3; ++ch) {
+                    const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
+                    const uint32_t e0 = s_lut[ch * 256 + (word & 0xFFu)];
+                    const uint32_t e1 = s_lut[ch * 256 + ((word >> 8) & 0xFFu)];
+                    const uint32_t e2 = s_lut[ch * 256 + ((word >> 16) & 0xFFu)];
+                    const uint32_t e3 = s_lut[ch * 256 + (word >> 24)];
+                    uint8_t* base = d.out + (((size_t)ch * crop_h + row) * crop_w) * 2;
+                    if (whole) {
+                        u32x2 v;
+                        int32_t col;
+                        if (d.flip) {
+                            col = (int32_t)crop_w - PPL - col0;
+                            v.x = e3 | (e2 << 16);
+                            v.y = e1 | (e0 << 16);
+                        } else {
+                            col = col0;
+                            v.x = e0 | (e1 << 16);
+                            v.y = e2 | (e3 << 16);
+                        }
+                        *reinterpret_cast<global_u32x2_any*>((uintptr_t)(base + (size_t)col * 2)) = v;
+                    } else {
+                        global_u16* out16 = reinterpret_cast<global_u16*>((uintptr_t)base);
 #pragma unroll
-                        for (int ch = 0; ch < 3; ++ch) {
-                            const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
-                            out16[((size_t)ch * crop_h + row) * crop_w + col] =
-                                s_lut[ch * 256 + ((word >> (8 * k)) & 0xFFu)];
+                        for (int k = 0; k < PPL; ++k) {
+                            int32_t col = col0 + k;
+                            if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
+                                if (d.flip) col = (int32_t)crop_w - 1 - col;
+                                out16[col] = (uint16_t)(k == 0 ? e0 : (k == 1 ? e1 : (k == 2 ? e2 : e3)));
+                            }
                         }
                     }
                 }
@@ -512,6 +541,16 @@ __global__ void l3_fill_u32_kernel(uint32_t* p, uint32_t n, uint32_t value) {
     if (i < n) p[i] = value;
 }
 
+/* Pulls the descriptor table from pinned host memory into device memory (words of
+ * 8 bytes) and clears the status words: one small kernel on the caller's stream, so
+ * that the decode kernel behind it depends on nothing but its predecessor. */
+__global__ void l3_prepare_kernel(const uint64_t* __restrict__ pinned_src, uint64_t* __restrict__ dst,
+                                  uint32_t words, uint32_t* status, uint32_t n_status) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < words) dst[i] = pinned_src[i];
+    if (status && i < n_status) status[i] = 0;
+}
+
 /* ---- host side: context, planning, launch ------------------------------- */
 
 constexpr int kSlots = 4;   /* descriptor staging slots: calls in flight before the host waits */
@@ -561,8 +600,6 @@ struct l3_ctx {
     L3ImageDesc* d_descs[kSlots] = {};    /* device */
     uint16_t* d_table[kSlots] = {};       /* device: 768-entry normalisation table */
     hipEvent_t done[kSlots] = {};         /* the slot's kernels have finished */
-    hipEvent_t copied[kSlots] = {};       /* the slot's descriptors are on the device */
-    hipStream_t copy_stream = nullptr;    /* descriptor uploads overlap the previous call's kernels */
     bool pending[kSlots] = {};
     int next = 0;
 };
@@ -716,7 +753,7 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     class_begin[3] = filled;
 
     /* Small batches travel inside the kernel arguments; larger ones through a device
-     * table that is uploaded on the context's own stream. */
+     * table that a small kernel on the caller's stream pulls from pinned host memory. */
     bool in_args = true;
     for (int k = 0; k < 3; ++k)
         if (class_begin[k + 1] - class_begin[k] > kArgDescs) in_args = false;
@@ -733,17 +770,18 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         }
     }
     if (!in_args) {
+        static_assert(sizeof(L3ImageDesc) % 8 == 0, "descriptor table is copied in 8-byte words");
         std::memcpy(ctx->h_stage[slot], stage, (size_t)n * sizeof(L3ImageDesc));
         d_descs = ctx->d_descs[slot];
-        if (hipMemcpyAsync(d_descs, ctx->h_stage[slot], (size_t)n * sizeof(L3ImageDesc),
-                           hipMemcpyHostToDevice, ctx->copy_stream) != hipSuccess ||
-            hipEventRecord(ctx->copied[slot], ctx->copy_stream) != hipSuccess ||
-            hipStreamWaitEvent(stream, ctx->copied[slot], 0) != hipSuccess)
-            return L3_ERR_DEVICE;
-    }
-    if (d_status)
+        const uint32_t words = (uint32_t)((size_t)n * sizeof(L3ImageDesc) / 8);
+        const uint32_t threads = words > (uint32_t)n ? words : (uint32_t)n;
+        hipLaunchKernelGGL(l3_prepare_kernel, dim3((threads + 255) / 256), dim3(256), 0, stream,
+                           reinterpret_cast<const uint64_t*>(ctx->h_stage[slot]),
+                           reinterpret_cast<uint64_t*>(d_descs), words, d_status, (uint32_t)n);
+    } else if (d_status) {
         hipLaunchKernelGGL(l3_fill_u32_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, d_status,
                            (uint32_t)n, 0u);
+    }
     const uint16_t* table = nullptr;
     if (mode == L3_MODE_TENSOR) {
         hipLaunchKernelGGL(l3_build_table_kernel, dim3(3), dim3(256), 0, stream, mean[0], mean[1],
@@ -792,14 +830,8 @@ l3_status l3_ctx_create(l3_ctx** out, int device) {
     l3_ctx* ctx = new (std::nothrow) l3_ctx;
     if (!ctx) return L3_ERR_DEVICE;
     ctx->device = device;
-    if (hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking) != hipSuccess) {
-        ctx->copy_stream = nullptr;
-        l3_ctx_destroy(ctx);
-        return L3_ERR_DEVICE;
-    }
     for (int s = 0; s < kSlots; ++s) {
         if (hipEventCreateWithFlags(&ctx->done[s], hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&ctx->copied[s], hipEventDisableTiming) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&ctx->d_table[s]), 768 * sizeof(uint16_t)) !=
                 hipSuccess) {
             l3_ctx_destroy(ctx);
@@ -816,12 +848,7 @@ void l3_ctx_destroy(l3_ctx* ctx) {
     for (int s = 0; s < kSlots; ++s) {
         if (ctx->pending[s]) (void)hipEventSynchronize(ctx->done[s]);
         if (ctx->done[s]) (void)hipEventDestroy(ctx->done[s]);
-        if (ctx->copied[s]) (void)hipEventDestroy(ctx->copied[s]);
         if (ctx->d_table[s]) (void)hipFree(ctx->d_table[s]);
-    }
-    if (ctx->copy_stream) {
-        (void)hipStreamSynchronize(ctx->copy_stream);
-        (void)hipStreamDestroy(ctx->copy_stream);
     }
     release_slots(ctx);
     std::free(ctx->scratch);
