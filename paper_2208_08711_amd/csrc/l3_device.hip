@@ -62,21 +62,26 @@ typedef __attribute__((address_space(1))) uint16_t global_u16;
 
 constexpr int kBlockThreads = 192;   /* three waves: one per colour channel */
 
-template <int N>
+template <int N, int PPL_>
 struct Geom {
     static_assert(N == 32 || N == 64 || N == 128, "patch sizes of the GPU path");
-    static constexpr int PPL = 4;                 /* pixels per lane */
+    static_assert(PPL_ == 4 || PPL_ == 8, "pixels per lane");
+    static constexpr int PPL = PPL_;              /* pixels per lane */
+    static constexpr int NW = PPL / 4;            /* 4-pixel words (32-bit delta windows) per lane */
+    static constexpr int NP = PPL / 2;            /* packed registers per lane */
     static constexpr int LPT = N / PPL;           /* lanes per patch */
     static constexpr int TPW = 64 / LPT;          /* patches per wave */
-    static constexpr int GPL = 2;                 /* 16-byte granules per lane per refill */
-    static constexpr int CHUNK = LPT * 16 * GPL;  /* bytes per refill of one stream (8N) */
+    static constexpr int CHUNK = 8 * N;           /* bytes per refill of one stream */
+    static constexpr int GPL = CHUNK / (LPT * 16); /* 16-byte granules per lane per refill */
     static constexpr int RING = 16 * N;           /* ring bytes per stream */
     static constexpr int RING_WORDS = RING / 4 + 4; /* + 16-byte mirror of the ring start */
     static constexpr int P = 3;                   /* rows per period = waves per workgroup */
+    static constexpr int QW = 64 * NW;            /* 4-pixel words per wave row */
     static constexpr int ROW_MAX = N + 3;         /* bytes a row can span: ceil((12 + 8N)/8) + 1 */
     static constexpr int AHEAD = P * ROW_MAX + 12; /* bytes a period may touch past its first row */
     /* one refill per period suffices, the first refill covers the first period
      * from any start alignment, and a refill never overwrites bytes still needed */
+    static_assert(GPL * LPT * 16 == CHUNK && GPL >= 1, "chunk is a whole number of granule rounds");
     static_assert(CHUNK >= P * ROW_MAX, "refill keeps up with the longest rows");
     static_assert(CHUNK >= 15 + AHEAD, "first refill covers the first period");
     static_assert(RING >= AHEAD + CHUNK + ROW_MAX + 8, "ring holds a row, a period ahead and a refill");
@@ -97,49 +102,56 @@ __device__ __forceinline__ uint32_t pk_mad_i16(uint32_t a, uint32_t b, uint32_t 
     return d;
 }
 
-/* Section 4.2, custom Paeth filter, on 2 x 2 pixels at once (two registers of
- * two 16-bit fields holding 0..255).  Value-wise the nearest of TL, TR, T to
- * TL + TR - T is: with lo = min(TL,TR), hi = max(TL,TR), dl = T - lo,
- * dh = hi - T (signed): lo if dl >= 2*dh, else hi if dh >= 2*dl, else T.  The
- * stated tie order (TL, TR, T) only ever chooses between equal values, except T
- * against a neighbour, where the neighbour wins: that is the ">=" above.
+/* Section 4.2, custom Paeth filter, on NP registers of two pixels at once (16-bit
+ * fields holding 0..255).  Value-wise the nearest of TL, TR, T to TL + TR - T is:
+ * with lo = min(TL,TR), hi = max(TL,TR), dl = T - lo, dh = hi - T (signed):
+ * lo if dl >= 2*dh, else hi if dh >= 2*dl, else T.  The stated tie order
+ * (TL, TR, T) only ever chooses between equal values, except T against a
+ * neighbour, where the neighbour wins: that is the ">=" above.
  * `border` has all ones in the fields whose pixel sits in the first or last
- * column of its patch, where the prediction is T.  The two registers are
- * worked on in lockstep so that dependent packed instructions are not adjacent. */
-struct Pred2 { uint32_t p0, p1; };
-__device__ __forceinline__ Pred2 predict4(uint32_t TL0, uint32_t TR0, uint32_t T0, uint32_t border0,
-                                          uint32_t TL1, uint32_t TR1, uint32_t T1, uint32_t border1) {
-    const u16x2 a0 = __builtin_bit_cast(u16x2, TL0), b0 = __builtin_bit_cast(u16x2, TR0),
-                c0 = __builtin_bit_cast(u16x2, T0);
-    const u16x2 a1 = __builtin_bit_cast(u16x2, TL1), b1 = __builtin_bit_cast(u16x2, TR1),
-                c1 = __builtin_bit_cast(u16x2, T1);
-    const u16x2 lo0 = __builtin_elementwise_min(a0, b0), lo1 = __builtin_elementwise_min(a1, b1);
-    const u16x2 hi0 = __builtin_elementwise_max(a0, b0), hi1 = __builtin_elementwise_max(a1, b1);
-    const uint32_t dl0 = __builtin_bit_cast(uint32_t, (u16x2)(c0 - lo0));
-    const uint32_t dl1 = __builtin_bit_cast(uint32_t, (u16x2)(c1 - lo1));
-    const uint32_t dh0 = __builtin_bit_cast(uint32_t, (u16x2)(hi0 - c0));
-    const uint32_t dh1 = __builtin_bit_cast(uint32_t, (u16x2)(hi1 - c1));
+ * column of its patch, where the prediction is T.  The registers are worked on
+ * in lockstep so that dependent packed instructions are not adjacent. */
+template <int NP>
+__device__ __forceinline__ void predict_pairs(const uint32_t (&TL)[NP], const uint32_t (&TR)[NP],
+                                              const uint32_t (&T)[NP], const uint32_t (&border)[NP],
+                                              uint32_t (&pred)[NP]) {
+    uint32_t L[NP], H[NP], dl[NP], dh[NP], not_lo[NP], not_hi[NP];
     const uint32_t minus2 = 0xFFFEFFFEu;
-    const s16x2 tl0 = __builtin_bit_cast(s16x2, pk_mad_i16(dh0, minus2, dl0));   /* dl - 2 dh */
-    const s16x2 tl1 = __builtin_bit_cast(s16x2, pk_mad_i16(dh1, minus2, dl1));
-    const s16x2 th0 = __builtin_bit_cast(s16x2, pk_mad_i16(dl0, minus2, dh0));   /* dh - 2 dl */
-    const s16x2 th1 = __builtin_bit_cast(s16x2, pk_mad_i16(dl1, minus2, dh1));
-    uint32_t not_lo0 = __builtin_bit_cast(uint32_t, (s16x2)(tl0 >> 15));
-    uint32_t not_lo1 = __builtin_bit_cast(uint32_t, (s16x2)(tl1 >> 15));
-    uint32_t not_hi0 = __builtin_bit_cast(uint32_t, (s16x2)(th0 >> 15));
-    uint32_t not_hi1 = __builtin_bit_cast(uint32_t, (s16x2)(th1 >> 15));
-    asm("" : "+v"(not_lo0), "+v"(not_lo1), "+v"(not_hi0), "+v"(not_hi1));   /* keep the masks packed */
-    const uint32_t H0 = __builtin_bit_cast(uint32_t, hi0), L0 = __builtin_bit_cast(uint32_t, lo0);
-    const uint32_t H1 = __builtin_bit_cast(uint32_t, hi1), L1 = __builtin_bit_cast(uint32_t, lo1);
+#pragma unroll
+    for (int j = 0; j < NP; ++j)
+        L[j] = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2, TL[j]),
+                                                                      __builtin_bit_cast(u16x2, TR[j])));
+#pragma unroll
+    for (int j = 0; j < NP; ++j)
+        H[j] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, TL[j]),
+                                                                      __builtin_bit_cast(u16x2, TR[j])));
+#pragma unroll
+    for (int j = 0; j < NP; ++j)
+        dl[j] = __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, T[j]) -
+                                                     __builtin_bit_cast(u16x2, L[j])));
+#pragma unroll
+    for (int j = 0; j < NP; ++j)
+        dh[j] = __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, H[j]) -
+                                                     __builtin_bit_cast(u16x2, T[j])));
+#pragma unroll
+    for (int j = 0; j < NP; ++j) not_lo[j] = pk_mad_i16(dh[j], minus2, dl[j]);   /* dl - 2 dh */
+#pragma unroll
+    for (int j = 0; j < NP; ++j) not_hi[j] = pk_mad_i16(dl[j], minus2, dh[j]);   /* dh - 2 dl */
+#pragma unroll
+    for (int j = 0; j < NP; ++j)
+        not_lo[j] = __builtin_bit_cast(uint32_t, (s16x2)(__builtin_bit_cast(s16x2, not_lo[j]) >> 15));
+#pragma unroll
+    for (int j = 0; j < NP; ++j)
+        not_hi[j] = __builtin_bit_cast(uint32_t, (s16x2)(__builtin_bit_cast(s16x2, not_hi[j]) >> 15));
+#pragma unroll
+    for (int j = 0; j < NP; ++j) asm("" : "+v"(not_lo[j]), "+v"(not_hi[j]));   /* keep the masks packed */
     /* bitop3 0xCA: first ? second : third */
-    const uint32_t r0 = __builtin_amdgcn_bitop3_b32(not_hi0, T0, H0, 0xCA);
-    const uint32_t r1 = __builtin_amdgcn_bitop3_b32(not_hi1, T1, H1, 0xCA);
-    const uint32_t q0 = __builtin_amdgcn_bitop3_b32(not_lo0, r0, L0, 0xCA);
-    const uint32_t q1 = __builtin_amdgcn_bitop3_b32(not_lo1, r1, L1, 0xCA);
-    Pred2 out;
-    out.p0 = __builtin_amdgcn_bitop3_b32(border0, T0, q0, 0xCA);
-    out.p1 = __builtin_amdgcn_bitop3_b32(border1, T1, q1, 0xCA);
-    return out;
+#pragma unroll
+    for (int j = 0; j < NP; ++j) pred[j] = __builtin_amdgcn_bitop3_b32(not_hi[j], T[j], H[j], 0xCA);
+#pragma unroll
+    for (int j = 0; j < NP; ++j) pred[j] = __builtin_amdgcn_bitop3_b32(not_lo[j], pred[j], L[j], 0xCA);
+#pragma unroll
+    for (int j = 0; j < NP; ++j) pred[j] = __builtin_amdgcn_bitop3_b32(border[j], T[j], pred[j], 0xCA);
 }
 
 /* The 32 stream bits starting at bit `bit` of a ring live in two aligned words
@@ -185,16 +197,16 @@ __device__ __forceinline__ void wave_lds_fence() {
 
 /* ---- the decode kernel ---------------------------------------------------- */
 
-template <int N, int MODE>
+template <int N, int PPL, int MODE>
 __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __restrict__ status,
                                             uint32_t crop_w, uint32_t crop_h,
                                             const uint16_t* __restrict__ lut) {
-    using G = Geom<N>;
-    constexpr int PPL = G::PPL, LPT = G::LPT, TPW = G::TPW, GPL = G::GPL;
+    using G = Geom<N, PPL>;
+    constexpr int LPT = G::LPT, TPW = G::TPW, GPL = G::GPL, NW = G::NW, NP = G::NP, QW = G::QW;
     constexpr int CHUNK = G::CHUNK, RING = G::RING, P = G::P;
 
     __shared__ __attribute__((aligned(16))) uint32_t rings[3][TPW][G::RING_WORDS];
-    __shared__ uint32_t parked[2][P][3][64];   /* [buffer][row of period][channel][lane] */
+    __shared__ __attribute__((aligned(8))) uint32_t parked[2][P][3][QW]; /* [buffer][row of period][channel][word] */
     __shared__ uint16_t s_lut[MODE == L3_MODE_TENSOR ? 768 : 2];
 
     if (MODE == L3_MODE_TENSOR) {
@@ -214,6 +226,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
     const bool active = txr < d.tile_x_count;
     const uint32_t tx = d.tile_x_first + (active ? txr : d.tile_x_count - 1);
     const uint32_t x0 = tx * N, y0 = ty * N;
+    const uint32_t strip_x0 = (d.tile_x_first + gx * TPW) * N;   /* first column of the wave's strip */
     const uint32_t pw = min((uint32_t)N, d.width - x0);
     uint32_t ph = min((uint32_t)N, d.height - y0);           /* same for the whole workgroup */
     if (MODE == L3_MODE_TENSOR)                              /* rows below the window are not needed */
@@ -259,40 +272,42 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
     }
     wave_lds_fence();
 
-    /* per-lane constants of the row loop */
+    /* The lane's pixels, 4 per word k (pixels 4k .. 4k+3 of the lane), sit in registers
+     * of two 16-bit fields: register 2k holds pixels (4k, 4k+2), register 2k+1 pixels
+     * (4k+1, 4k+3).  Then the top-right neighbours of an even register are the odd
+     * register beside it and the top-left neighbours of an odd register the even one;
+     * the other neighbours take one alignbit, the two outermost a lane shift. */
     const uint32_t xpix = xl * PPL;                         /* first pixel column of this lane */
-    /* The lane's 4 pixels sit in two registers of two 16-bit fields: register 0 holds
-     * pixels (0, 2), register 1 pixels (1, 3).  Then the top-right neighbours of
-     * register 0 are register 1 itself and the top-left neighbours of register 1 are
-     * register 0; only the two outer neighbours need a lane shift. */
-    uint32_t border[2];
+    uint32_t border[NP];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const uint32_t xa = xpix + j, xb = xa + 2;
+    for (int j = 0; j < NP; ++j) {
+        const uint32_t xa = xpix + 4 * (j / 2) + (j & 1), xb = xa + 2;
         border[j] = ((xa == 0 || xa + 1 == pw) ? 0x0000FFFFu : 0u) |
                     ((xb == 0 || xb + 1 == pw) ? 0xFFFF0000u : 0u);
     }
-    const uint32_t nvalid = !active ? 0u : (xpix >= pw ? 0u : min((uint32_t)PPL, pw - xpix));
 
     /* what the arithmetic of a row needs from its base-delta record */
-    uint32_t w, w2, w3, base2, xbit, wmax = 0;
-    uint32_t xwhere;   /* LDS address of the words holding this lane's deltas of the open row */
-    uint32_t hwhere;   /* LDS address of the words holding the record after the open row */
+    uint32_t w, w2, w3, base2, xbit[NW], wmax = 0;
+    uint32_t xwhere[NW];   /* LDS addresses of the words holding this lane's deltas of the open row */
+    uint32_t hwhere;       /* LDS address of the words holding the record after the open row */
     const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)ring;
 
     /* Opens the row whose record (4-bit width, 8-bit base) is at bitpos: works out
-     * where this lane's 4 deltas are (4w <= 32 contiguous bits) and advances bitpos
-     * to the next record.  A width above 8 (damaged stream) is not clamped: ring
-     * indices are masked and global loads are bounded by the file, so it can only
-     * produce wrong pixels. */
+     * where this lane's deltas are (4w <= 32 contiguous bits per word of 4 pixels) and
+     * advances bitpos to the next record.  A width above 8 (damaged stream) is not
+     * clamped: ring indices are masked and global loads are bounded by the file, so it
+     * can only produce wrong pixels. */
     auto open_row = [&](RingWords hw) {
         const uint32_t hdr = ring_align(hw, bitpos);
         const uint32_t wr = hdr & 15u;
         const uint32_t base = __builtin_amdgcn_ubfe(hdr, 4, 8);
         const uint32_t dbit = bitpos + 12;
         bitpos = dbit + pw * wr;
-        xbit = dbit + xpix * wr;
-        xwhere = ring_where<RING>(ring_lds, xbit);
+        xbit[0] = dbit + xpix * wr;
+#pragma unroll
+        for (int k = 1; k < NW; ++k) xbit[k] = xbit[k - 1] + 4 * wr;
+#pragma unroll
+        for (int k = 0; k < NW; ++k) xwhere[k] = ring_where<RING>(ring_lds, xbit[k]);
         hwhere = ring_where<RING>(ring_lds, bitpos);
         w = wr;
         w2 = wr + wr;
@@ -301,84 +316,92 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
     };
 
     /* After the workgroup barrier: this wave writes row c of the period whose rows
-     * are parked in buffer `buf` (rows first .. first+count-1 of the patch). */
+     * are parked in buffer `buf` (rows first .. first+count-1 of the patch).  Lane l
+     * takes the 4-pixel words l, l + 64, ... of the wave's strip: 12 contiguous
+     * output bytes each, contiguous over the lanes. */
     auto flush = [&](uint32_t buf, uint32_t first, uint32_t count) {
         if (c >= count) return;
         const uint32_t y = y0 + first + c;
-        const uint32_t* src = &parked[buf][c][0][lane];
-        const uint32_t pr = src[0], pg = src[64], pb = src[128];   /* 4 pixels of R, G, B */
-        if (MODE == L3_MODE_HWC) {
-            uint8_t* dst = d.out + (size_t)y * d.row_stride + (size_t)(x0 + xpix) * 3;
-            /* R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3 */
-            const uint32_t t0 = __builtin_amdgcn_perm(pg, pr, 0x010c0400u);
-            const uint32_t o0 = __builtin_amdgcn_perm(pb, t0, 0x03040100u);
-            const uint32_t t1 = __builtin_amdgcn_perm(pb, pg, 0x020c0501u);
-            const uint32_t o1 = __builtin_amdgcn_perm(pr, t1, 0x03060100u);
-            const uint32_t t2 = __builtin_amdgcn_perm(pr, pb, 0x030c0702u);
-            const uint32_t o2 = __builtin_amdgcn_perm(pg, t2, 0x03070100u);
-            if (nvalid == PPL) {
-                const u32x3 v = {o0, o1, o2};
-                *reinterpret_cast<global_u32x3_any*>((uintptr_t)dst) = v;
-            } else if (nvalid) {
-                global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
 #pragma unroll
-                for (int k = 0; k < 9; ++k) {
-                    const uint32_t word = k < 4 ? o0 : (k < 8 ? o1 : o2);
-                    if ((uint32_t)k < 3 * nvalid) b[k] = (uint8_t)(word >> (8 * (k & 3)));
-                }
-            }
-        } else if (MODE == L3_MODE_CHW) {
-#pragma unroll
-            for (int ch = 0; ch < 3; ++ch) {
-                const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
-                uint8_t* dst = d.out + (size_t)ch * d.plane_stride + (size_t)y * d.row_stride + x0 + xpix;
-                if (nvalid == PPL) {
-                    *reinterpret_cast<global_u32_any*>((uintptr_t)dst) = word;
+        for (int pass = 0; pass < NW; ++pass) {
+            const uint32_t q = lane + 64 * pass;
+            const uint32_t x = strip_x0 + 4 * q;                       /* image column of the word */
+            const uint32_t nvalid = x >= d.width ? 0u : min(4u, d.width - x);
+            const uint32_t* src = &parked[buf][c][0][q];
+            const uint32_t pr = src[0], pg = src[QW], pb = src[2 * QW];   /* 4 pixels of R, G, B */
+            if (MODE == L3_MODE_HWC) {
+                uint8_t* dst = d.out + (size_t)y * d.row_stride + (size_t)x * 3;
+                /* R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3 */
+                const uint32_t t0 = __builtin_amdgcn_perm(pg, pr, 0x010c0400u);
+                const uint32_t o0 = __builtin_amdgcn_perm(pb, t0, 0x03040100u);
+                const uint32_t t1 = __builtin_amdgcn_perm(pb, pg, 0x020c0501u);
+                const uint32_t o1 = __builtin_amdgcn_perm(pr, t1, 0x03060100u);
+                const uint32_t t2 = __builtin_amdgcn_perm(pr, pb, 0x030c0702u);
+                const uint32_t o2 = __builtin_amdgcn_perm(pg, t2, 0x03070100u);
+                if (nvalid == 4) {
+                    const u32x3 v = {o0, o1, o2};
+                    *reinterpret_cast<global_u32x3_any*>((uintptr_t)dst) = v;
                 } else if (nvalid) {
                     global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
 #pragma unroll
-                    for (int k = 0; k < 3; ++k)
-                        if ((uint32_t)k < nvalid) b[k] = (uint8_t)(word >> (8 * k));
+                    for (int k = 0; k < 9; ++k) {
+                        const uint32_t word = k < 4 ? o0 : (k < 8 ? o1 : o2);
+                        if ((uint32_t)k < 3 * nvalid) b[k] = (uint8_t)(word >> (8 * (k & 3)));
+                    }
                 }
-            }
-        } else {
-            /* tensor mode: window test, optional mirror, table of the 256 normalised
-             * values.  A lane whose 4 pixels all lie inside the window writes 4 elements
-             * (8 bytes) per channel at once, mirrored or not; edge lanes go element by
-             * element. */
-            const int32_t row = (int32_t)y - d.crop_y0;
-            if (row >= 0 && row < (int32_t)crop_h && nvalid) {
-                const int32_t col0 = (int32_t)(x0 + xpix) - d.crop_x0;   /* window column of pixel 0 */
-                const bool whole = nvalid == PPL && col0 >= 0 && col0 + PPL <= (int32_t)crop_w;
+            } else if (MODE == L3_MODE_CHW) {
 #pragma unroll
                 for (int ch = 0; ch < 3; ++ch) {
                     const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
-                    const uint32_t e0 = s_lut[ch * 256 + (word & 0xFFu)];
-                    const uint32_t e1 = s_lut[ch * 256 + ((word >> 8) & 0xFFu)];
-                    const uint32_t e2 = s_lut[ch * 256 + ((word >> 16) & 0xFFu)];
-                    const uint32_t e3 = s_lut[ch * 256 + (word >> 24)];
-                    uint8_t* base = d.out + (((size_t)ch * crop_h + row) * crop_w) * 2;
-                    if (whole) {
-                        u32x2 v;
-                        int32_t col;
-                        if (d.flip) {
-                            col = (int32_t)crop_w - PPL - col0;
-                            v.x = e3 | (e2 << 16);
-                            v.y = e1 | (e0 << 16);
-                        } else {
-                            col = col0;
-                            v.x = e0 | (e1 << 16);
-                            v.y = e2 | (e3 << 16);
-                        }
-                        *reinterpret_cast<global_u32x2_any*>((uintptr_t)(base + (size_t)col * 2)) = v;
-                    } else {
-                        global_u16* out16 = reinterpret_cast<global_u16*>((uintptr_t)base);
+                    uint8_t* dst = d.out + (size_t)ch * d.plane_stride + (size_t)y * d.row_stride + x;
+                    if (nvalid == 4) {
+                        *reinterpret_cast<global_u32_any*>((uintptr_t)dst) = word;
+                    } else if (nvalid) {
+                        global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
 #pragma unroll
-                        for (int k = 0; k < PPL; ++k) {
-                            int32_t col = col0 + k;
-                            if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
-                                if (d.flip) col = (int32_t)crop_w - 1 - col;
-                                out16[col] = (uint16_t)(k == 0 ? e0 : (k == 1 ? e1 : (k == 2 ? e2 : e3)));
+                        for (int k = 0; k < 3; ++k)
+                            if ((uint32_t)k < nvalid) b[k] = (uint8_t)(word >> (8 * k));
+                    }
+                }
+            } else {
+                /* tensor mode: window test, optional mirror, table of the 256 normalised
+                 * values.  A word whose 4 pixels all lie inside the window is written as 4
+                 * elements (8 bytes) per channel at once, mirrored or not; words on the
+                 * window's edge go element by element. */
+                const int32_t row = (int32_t)y - d.crop_y0;
+                if (row >= 0 && row < (int32_t)crop_h && nvalid) {
+                    const int32_t col0 = (int32_t)x - d.crop_x0;   /* window column of pixel 0 */
+                    const bool whole = nvalid == 4 && col0 >= 0 && col0 + 4 <= (int32_t)crop_w;
+#pragma unroll
+                    for (int ch = 0; ch < 3; ++ch) {
+                        const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
+                        const uint32_t e0 = s_lut[ch * 256 + (word & 0xFFu)];
+                        const uint32_t e1 = s_lut[ch * 256 + ((word >> 8) & 0xFFu)];
+                        const uint32_t e2 = s_lut[ch * 256 + ((word >> 16) & 0xFFu)];
+                        const uint32_t e3 = s_lut[ch * 256 + (word >> 24)];
+                        uint8_t* base = d.out + (((size_t)ch * crop_h + row) * crop_w) * 2;
+                        if (whole) {
+                            u32x2 v;
+                            int32_t col;
+                            if (d.flip) {
+                                col = (int32_t)crop_w - 4 - col0;
+                                v.x = e3 | (e2 << 16);
+                                v.y = e1 | (e0 << 16);
+                            } else {
+                                col = col0;
+                                v.x = e0 | (e1 << 16);
+                                v.y = e2 | (e3 << 16);
+                            }
+                            *reinterpret_cast<global_u32x2_any*>((uintptr_t)(base + (size_t)col * 2)) = v;
+                        } else {
+                            global_u16* out16 = reinterpret_cast<global_u16*>((uintptr_t)base);
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                int32_t col = col0 + k;
+                                if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
+                                    if (d.flip) col = (int32_t)crop_w - 1 - col;
+                                    out16[col] = (uint16_t)(k == 0 ? e0 : (k == 1 ? e1 : (k == 2 ? e2 : e3)));
+                                }
                             }
                         }
                     }
@@ -387,48 +410,62 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
         }
     };
 
-    uint32_t prev0 = 0, prev1 = 0;   /* an all-zero row above predicts 0: row 0 is raw */
+    uint32_t prev[NP];
+#pragma unroll
+    for (int j = 0; j < NP; ++j) prev[j] = 0;   /* an all-zero row above predicts 0: row 0 is raw */
     open_row(ring_fetch(ring_where<RING>(ring_lds, bitpos)));
 
     /* One row: no branch inside.  The deltas of the row and the record of the next
      * row travel from LDS while part 1 is computed; after the last row the record
-     * read does not exist, which is harmless.  `park` is where this wave parks the
-     * row (one word p0 p1 p2 p3). */
+     * read does not exist, which is harmless.  `park` is where this lane parks its
+     * NW words (p0 p1 p2 p3 each). */
     auto do_row = [&](uint32_t* park) {
-        const RingWords xw = ring_fetch(xwhere);
+        RingWords xw[NW];
+#pragma unroll
+        for (int k = 0; k < NW; ++k) xw[k] = ring_fetch(xwhere[k]);
         const RingWords hdr_next = ring_fetch(hwhere);
         __builtin_amdgcn_sched_barrier(0);
 
         /* inverse filter, part 1: the prediction depends only on the row above
          * (registers + lane neighbours) */
-        const uint32_t from_left = dpp_from_lower_lane(prev1);    /* pixels (1,3) of the lane below */
-        const uint32_t from_right = dpp_from_upper_lane(prev0);   /* pixels (0,2) of the lane above */
-        /* pixels (0,2): top-left = (3 of the lower lane, 1), top-right = (1,3);
-         * pixels (1,3): top-left = (0,2), top-right = (2, 0 of the upper lane) */
-        const Pred2 pr = predict4(__builtin_amdgcn_alignbit(prev1, from_left, 16), prev1, prev0, border[0],
-                                  prev0, __builtin_amdgcn_alignbit(from_right, prev0, 16), prev1, border[1]);
-        const uint32_t pred0 = pr.p0, pred1 = pr.p1;
+        const uint32_t from_left = dpp_from_lower_lane(prev[NP - 1]);   /* pixels (PPL-3, PPL-1) of the lane below */
+        const uint32_t from_right = dpp_from_upper_lane(prev[0]);       /* pixels (0, 2) of the lane above */
+        uint32_t TL[NP], TR[NP], pred[NP];
+#pragma unroll
+        for (int k = 0; k < NW; ++k) {
+            const uint32_t E = prev[2 * k], O = prev[2 * k + 1];
+            /* pixels (4k, 4k+2): top-left = (4k-1, 4k+1), top-right = (4k+1, 4k+3) */
+            TL[2 * k] = __builtin_amdgcn_alignbit(O, k > 0 ? prev[2 * k - 1] : from_left, 16);
+            TR[2 * k] = O;
+            /* pixels (4k+1, 4k+3): top-left = (4k, 4k+2), top-right = (4k+2, 4k+4) */
+            TL[2 * k + 1] = E;
+            TR[2 * k + 1] = __builtin_amdgcn_alignbit(k < NW - 1 ? prev[2 * k + 2] : from_right, E, 16);
+        }
+        predict_pairs<NP>(TL, TR, prev, border, pred);
         __builtin_amdgcn_sched_barrier(0);
 
         /* base-delta: value = base + delta; part 2 of the filter: pixel = prediction
          * + value (both mod 256, one mask at the end) */
         wmax = max(wmax, w);
-        const uint32_t x = ring_align(xw, xbit);
-        const uint32_t d0 = __builtin_amdgcn_ubfe(x, 0, w);
-        const uint32_t d1 = __builtin_amdgcn_ubfe(x, w, w);
-        const uint32_t d2 = __builtin_amdgcn_ubfe(x, w2, w);
-        const uint32_t d3 = __builtin_amdgcn_ubfe(x, w3, w);
-        prev0 = (pred0 + (d0 | (d2 << 16)) + base2) & 0x00FF00FFu;
-        prev1 = (pred1 + (d1 | (d3 << 16)) + base2) & 0x00FF00FFu;
-        *park = __builtin_amdgcn_perm(prev1, prev0, 0x06020400u);   /* p0 p1 p2 p3 */
+        uint32_t word[NW];
+#pragma unroll
+        for (int k = 0; k < NW; ++k) {
+            const uint32_t x = ring_align(xw[k], xbit[k]);
+            const uint32_t d0 = __builtin_amdgcn_ubfe(x, 0, w);
+            const uint32_t d1 = __builtin_amdgcn_ubfe(x, w, w);
+            const uint32_t d2 = __builtin_amdgcn_ubfe(x, w2, w);
+            const uint32_t d3 = __builtin_amdgcn_ubfe(x, w3, w);
+            prev[2 * k] = (pred[2 * k] + (d0 | (d2 << 16)) + base2) & 0x00FF00FFu;
+            prev[2 * k + 1] = (pred[2 * k + 1] + (d1 | (d3 << 16)) + base2) & 0x00FF00FFu;
+            word[k] = __builtin_amdgcn_perm(prev[2 * k + 1], prev[2 * k], 0x06020400u);   /* p0 p1 p2 p3 */
+        }
+#pragma unroll
+        for (int k = 0; k < NW; ++k) park[k] = word[k];
 
         __builtin_amdgcn_sched_barrier(0);
         open_row(hdr_next);
     };
 
-    /* Periods of P = 3 rows, unrolled so that the row's place in the period is a
-     * constant: the previous period is written out before row 0, the ring is topped
-     * up before row 2.  Only the last period can be shorter. */
     /* Waves that are ahead yield to waves that are behind (the hardware otherwise
      * favours the oldest wave, and the youngest ones would finish the kernel alone):
      * the wave's issue priority drops by one in each quarter of its rows. */
@@ -436,6 +473,9 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
     uint32_t next_drop = quarter, stage = 0;
     __builtin_amdgcn_s_setprio(3);
 
+    /* Periods of P = 3 rows, unrolled so that the row's place in the period is a
+     * constant: the previous period is written out before row 0, the ring is topped
+     * up before row 2.  Only the last period can be shorter. */
     uint32_t buf = 0;
     for (uint32_t r = 0; r < ph; r += P) {
         const uint32_t rows = min((uint32_t)P, ph - r);
@@ -451,9 +491,9 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
             __syncthreads();
             flush(buf ^ 1u, r - P, P);
         }
-        uint32_t* park = &parked[buf][0][c][lane];
+        uint32_t* park = &parked[buf][0][c][lane * NW];
         do_row(park);
-        if (rows > 1) do_row(park + 3 * 64);
+        if (rows > 1) do_row(park + 3 * QW);
         if (rows > 2) {
             if (r + P < ph) {
                 /* top the ring up for rows r+3 .. r+5; bitpos is the record of row r+3 */
@@ -473,7 +513,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                 }
                 wave_lds_fence();
             }
-            do_row(park + 2 * 3 * 64);
+            do_row(park + 2 * 3 * QW);
         }
         buf ^= 1u;
     }
@@ -490,11 +530,11 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
 }
 
 /* Descriptors in a device table (any batch size)... */
-template <int N, int MODE>
+template <int N, int PPL, int MODE>
 __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel(
     const L3ImageDesc* __restrict__ descs, uint32_t* __restrict__ status, uint32_t crop_w,
     uint32_t crop_h, const uint16_t* __restrict__ lut) {
-    decode_unit<N, MODE>(descs[blockIdx.y], status, crop_w, crop_h, lut);
+    decode_unit<N, PPL, MODE>(descs[blockIdx.y], status, crop_w, crop_h, lut);
 }
 
 /* ...or, for small batches, inside the kernel arguments: no upload, no dependency
@@ -503,11 +543,11 @@ constexpr int kArgDescs = 32;
 struct DescPack { L3ImageDesc d[kArgDescs]; };
 static_assert(sizeof(DescPack) + 64 <= 4096, "kernel argument segment");
 
-template <int N, int MODE>
+template <int N, int PPL, int MODE>
 __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel_args(
     const DescPack pack, uint32_t* __restrict__ status, uint32_t crop_w, uint32_t crop_h,
     const uint16_t* __restrict__ lut) {
-    decode_unit<N, MODE>(pack.d[blockIdx.y], status, crop_w, crop_h, lut);
+    decode_unit<N, PPL, MODE>(pack.d[blockIdx.y], status, crop_w, crop_h, lut);
 }
 
 /* y = (x/255 - mean) / stdv for all 256 byte values of each channel, IEEE
@@ -556,37 +596,55 @@ __global__ void l3_prepare_kernel(const uint64_t* __restrict__ pinned_src, uint6
 constexpr int kSlots = 4;   /* descriptor staging slots: calls in flight before the host waits */
 
 typedef void (*decode_kernel_t)(const L3ImageDesc*, uint32_t*, uint32_t, uint32_t, const uint16_t*);
-
-template <int N>
-decode_kernel_t kernel_for_mode(int mode) {
-    switch (mode) {
-        case L3_MODE_HWC: return l3_decode_kernel<N, L3_MODE_HWC>;
-        case L3_MODE_CHW: return l3_decode_kernel<N, L3_MODE_CHW>;
-        default: return l3_decode_kernel<N, L3_MODE_TENSOR>;
-    }
-}
-
 typedef void (*decode_kernel_args_t)(const DescPack, uint32_t*, uint32_t, uint32_t, const uint16_t*);
 
-template <int N>
-decode_kernel_args_t kernel_args_for_mode(int mode) {
+struct KernelChoice {
+    decode_kernel_t table;        /* descriptors in a device table */
+    decode_kernel_args_t args;    /* descriptors in the kernel arguments */
+    int tiles_per_wave;
+};
+
+template <int N, int PPL>
+KernelChoice choice_for_mode(int mode) {
+    KernelChoice k;
+    k.tiles_per_wave = Geom<N, PPL>::TPW;
     switch (mode) {
-        case L3_MODE_HWC: return l3_decode_kernel_args<N, L3_MODE_HWC>;
-        case L3_MODE_CHW: return l3_decode_kernel_args<N, L3_MODE_CHW>;
-        default: return l3_decode_kernel_args<N, L3_MODE_TENSOR>;
+        case L3_MODE_HWC:
+            k.table = l3_decode_kernel<N, PPL, L3_MODE_HWC>;
+            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_HWC>;
+            break;
+        case L3_MODE_CHW:
+            k.table = l3_decode_kernel<N, PPL, L3_MODE_CHW>;
+            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_CHW>;
+            break;
+        default:
+            k.table = l3_decode_kernel<N, PPL, L3_MODE_TENSOR>;
+            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_TENSOR>;
+            break;
     }
+    return k;
 }
 
-decode_kernel_args_t pick_kernel_args(int n, int mode) {
-    if (n == 32) return kernel_args_for_mode<32>(mode);
-    if (n == 64) return kernel_args_for_mode<64>(mode);
-    return kernel_args_for_mode<128>(mode);
+/* Pixels per lane.  Both variants are kept: on MI355X 4 measured faster on every
+ * benchmark workload (more, smaller waves hide latency better than the 12 % fewer
+ * vector instructions of 8 buy).  L3_PIXELS_PER_LANE=8 in the environment selects
+ * the other one. */
+int pixels_per_lane(int n, int mode) {
+    (void)n;
+    (void)mode;
+    const char* e = std::getenv("L3_PIXELS_PER_LANE");
+    return (e && e[0] == '8' && e[1] == 0) ? 8 : 4;
 }
 
-decode_kernel_t pick_kernel(int n, int mode, int* tiles_per_wave) {
-    if (n == 32) { *tiles_per_wave = Geom<32>::TPW; return kernel_for_mode<32>(mode); }
-    if (n == 64) { *tiles_per_wave = Geom<64>::TPW; return kernel_for_mode<64>(mode); }
-    *tiles_per_wave = Geom<128>::TPW; return kernel_for_mode<128>(mode);
+KernelChoice pick_kernel(int n, int mode) {
+    if (pixels_per_lane(n, mode) == 8) {
+        if (n == 32) return choice_for_mode<32, 8>(mode);
+        if (n == 64) return choice_for_mode<64, 8>(mode);
+        return choice_for_mode<128, 8>(mode);
+    }
+    if (n == 32) return choice_for_mode<32, 4>(mode);
+    if (n == 64) return choice_for_mode<64, 4>(mode);
+    return choice_for_mode<128, 4>(mode);
 }
 
 }  // namespace
@@ -701,8 +759,7 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     uint32_t max_units[3] = {0, 0, 0};
     for (int k = 0; k < 3; ++k) {
         class_begin[k] = filled;
-        int tpw = 1;
-        (void)pick_kernel(kClasses[k], mode, &tpw);
+        const int tpw = pick_kernel(kClasses[k], mode).tiles_per_wave;
         for (int i = 0; i < n; ++i) {
             if (k == 0) {   /* validate everything before anything is enqueued */
                 L3ImageDesc probe;
@@ -795,12 +852,11 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         if (in_args) {
             DescPack pack;
             std::memcpy(pack.d, stage + class_begin[k], (size_t)count * sizeof(L3ImageDesc));
-            hipLaunchKernelGGL(pick_kernel_args(kClasses[k], mode), dim3(gx, (uint32_t)count),
+            hipLaunchKernelGGL(pick_kernel(kClasses[k], mode).args, dim3(gx, (uint32_t)count),
                                dim3(kBlockThreads), 0, stream, pack, d_status, crop_w, crop_h, table);
             continue;
         }
-        int tpw = 1;
-        decode_kernel_t kern = pick_kernel(kClasses[k], mode, &tpw);
+        decode_kernel_t kern = pick_kernel(kClasses[k], mode).table;
         for (int first = 0; first < count; first += 65535) {
             const int m = count - first < 65535 ? count - first : 65535;
             hipLaunchKernelGGL(kern, dim3(gx, (uint32_t)m), dim3(kBlockThreads), 0, stream,

@@ -156,6 +156,23 @@ def test_config3_full_batch_bench_configuration(l3, ctx):
     check_batch(l3, ctx, synth.config3(32))
 
 
+@pytest.mark.parametrize("ppl", ["4", "8"])
+def test_both_lane_widths(l3, ctx, ppl, monkeypatch):
+    """The kernel exists with 4 and with 8 pixels per lane; the library picks one per
+    patch size.  Force each for every patch size, in all three output modes."""
+    monkeypatch.setenv("L3_PIXELS_PER_LANE", ppl)
+    images = [synth.cosine_field(900 + k, w, h) for k, (w, h) in
+              enumerate([(450, 337), (129, 127), (33, 70), (1, 1), (260, 131)])]
+    images.append(synth.uniform_bytes(950, 300, 200))
+    for patch in (32, 64, 128):
+        check_batch(l3, ctx, images, patch=patch, layout="hwc", pad_cols=3)
+        check_batch(l3, ctx, images, patch=patch, layout="chw", pad_cols=3)
+    im = synth.cosine_field(960, 300, 260)
+    for patch in (32, 64, 128):
+        crops = [(0, 0, 0), (76, 36, 1), (37, 19, 1), (5, 30, 0)]
+        tensor_case(l3, ctx, [im] * len(crops), crops, 224, 0, patch=patch)
+
+
 def test_mixed_patch_sizes_in_one_call(l3, ctx):
     images = [synth.cosine_field(51, 300, 200), synth.cosine_field(52, 300, 200),
               synth.cosine_field(53, 300, 200)]
