@@ -315,6 +315,25 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
         base2 = base | (base << 16);
     };
 
+    /* What the write-out needs from the descriptor, pinned in registers: left to
+     * itself the compiler reloads these from the argument segment after every
+     * barrier, and the wave waits for the scalar load each period. */
+    uint64_t out_base = (uint64_t)(uintptr_t)d.out, out_row_stride = d.row_stride,
+             out_plane_stride = d.plane_stride;
+    uint32_t img_width = d.width;
+    int32_t win_x0 = d.crop_x0, win_y0 = d.crop_y0;
+    uint32_t win_flip = d.flip;
+    asm volatile("" : "+s"(out_base), "+s"(out_row_stride), "+s"(out_plane_stride), "+s"(img_width),
+                      "+s"(win_x0), "+s"(win_y0), "+s"(win_flip));
+    /* lane l takes the 4-pixel words l, l + 64, ... of the wave's strip; how many of
+     * their pixels exist does not change from row to row */
+    uint32_t word_x[NW], word_valid[NW];
+#pragma unroll
+    for (int pass = 0; pass < NW; ++pass) {
+        word_x[pass] = strip_x0 + 4 * (lane + 64 * pass);
+        word_valid[pass] = word_x[pass] >= img_width ? 0u : min(4u, img_width - word_x[pass]);
+    }
+
     /* After the workgroup barrier: this wave writes row c of the period whose rows
      * are parked in buffer `buf` (rows first .. first+count-1 of the patch).  Lane l
      * takes the 4-pixel words l, l + 64, ... of the wave's strip: 12 contiguous
@@ -325,12 +344,12 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
 #pragma unroll
         for (int pass = 0; pass < NW; ++pass) {
             const uint32_t q = lane + 64 * pass;
-            const uint32_t x = strip_x0 + 4 * q;                       /* image column of the word */
-            const uint32_t nvalid = x >= d.width ? 0u : min(4u, d.width - x);
+            const uint32_t x = word_x[pass];                           /* image column of the word */
+            const uint32_t nvalid = word_valid[pass];
             const uint32_t* src = &parked[buf][c][0][q];
             const uint32_t pr = src[0], pg = src[QW], pb = src[2 * QW];   /* 4 pixels of R, G, B */
             if (MODE == L3_MODE_HWC) {
-                uint8_t* dst = d.out + (size_t)y * d.row_stride + (size_t)x * 3;
+                uint8_t* dst = reinterpret_cast<uint8_t*>((uintptr_t)(out_base + (uint64_t)y * out_row_stride + (uint64_t)x * 3));
                 /* R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3 */
                 const uint32_t t0 = __builtin_amdgcn_perm(pg, pr, 0x010c0400u);
                 const uint32_t o0 = __builtin_amdgcn_perm(pb, t0, 0x03040100u);
@@ -353,7 +372,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
 #pragma unroll
                 for (int ch = 0; ch < 3; ++ch) {
                     const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
-                    uint8_t* dst = d.out + (size_t)ch * d.plane_stride + (size_t)y * d.row_stride + x;
+                    uint8_t* dst = reinterpret_cast<uint8_t*>((uintptr_t)(out_base + (uint64_t)ch * out_plane_stride + (uint64_t)y * out_row_stride + x));
                     if (nvalid == 4) {
                         *reinterpret_cast<global_u32_any*>((uintptr_t)dst) = word;
                     } else if (nvalid) {
@@ -368,9 +387,9 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                  * values.  A word whose 4 pixels all lie inside the window is written as 4
                  * elements (8 bytes) per channel at once, mirrored or not; words on the
                  * window's edge go element by element. */
-                const int32_t row = (int32_t)y - d.crop_y0;
+                const int32_t row = (int32_t)y - win_y0;
                 if (row >= 0 && row < (int32_t)crop_h && nvalid) {
-                    const int32_t col0 = (int32_t)x - d.crop_x0;   /* window column of pixel 0 */
+                    const int32_t col0 = (int32_t)x - win_x0;   /* window column of pixel 0 */
                     const bool whole = nvalid == 4 && col0 >= 0 && col0 + 4 <= (int32_t)crop_w;
 #pragma unroll
                     for (int ch = 0; ch < 3; ++ch) {
@@ -379,11 +398,11 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                         const uint32_t e1 = s_lut[ch * 256 + ((word >> 8) & 0xFFu)];
                         const uint32_t e2 = s_lut[ch * 256 + ((word >> 16) & 0xFFu)];
                         const uint32_t e3 = s_lut[ch * 256 + (word >> 24)];
-                        uint8_t* base = d.out + (((size_t)ch * crop_h + row) * crop_w) * 2;
+                        uint8_t* base = reinterpret_cast<uint8_t*>((uintptr_t)(out_base + (((uint64_t)ch * crop_h + row) * crop_w) * 2));
                         if (whole) {
                             u32x2 v;
                             int32_t col;
-                            if (d.flip) {
+                            if (win_flip) {
                                 col = (int32_t)crop_w - 4 - col0;
                                 v.x = e3 | (e2 << 16);
                                 v.y = e1 | (e0 << 16);
@@ -399,7 +418,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                             for (int k = 0; k < 4; ++k) {
                                 int32_t col = col0 + k;
                                 if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
-                                    if (d.flip) col = (int32_t)crop_w - 1 - col;
+                                    if (win_flip) col = (int32_t)crop_w - 1 - col;
                                     out16[col] = (uint16_t)(k == 0 ? e0 : (k == 1 ? e1 : (k == 2 ? e2 : e3)));
                                 }
                             }
