@@ -65,6 +65,51 @@ def make_workload(name):
     raise SystemExit(f"unknown workload {name}")
 
 
+def measure_overlap(torch, step, stream, steps, decode_alone_ms):
+    """Decode steps on `stream`, a bf16 GEMM loop on a second stream (both default
+    priority): each alone and both together."""
+    side = torch.cuda.Stream()
+    m = 8192
+    a = torch.randn((m, m), dtype=torch.bfloat16, device="cuda")
+    b = torch.randn((m, m), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty((m, m), dtype=torch.bfloat16, device="cuda")
+
+    def gemms(k):
+        with torch.cuda.stream(side):
+            for _ in range(k):
+                torch.matmul(a, b, out=out)
+
+    gemms(5)
+    torch.cuda.synchronize()
+    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g0.record(side)
+    gemms(20)
+    g1.record(side)
+    torch.cuda.synchronize()
+    gemm_alone_ms = g0.elapsed_time(g1) / 20
+    # together: enough GEMMs to cover the decode steps
+    n_gemm = max(4, int(steps * decode_alone_ms / gemm_alone_ms) + 2)
+    d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g0.record(side)
+    d0.record(stream)
+    done_g = 0
+    for k in range(steps):
+        step(k)
+        want = (k + 1) * n_gemm // steps
+        if want > done_g:
+            gemms(want - done_g)
+            done_g = want
+    d1.record(stream)
+    g1.record(side)
+    torch.cuda.synchronize()
+    return {"compute": "torch.matmul bf16 %dx%dx%d on a second stream, default priority" % (m, m, m),
+            "decode_ms_per_step_alone": decode_alone_ms,
+            "decode_ms_per_step_beside_compute": d0.elapsed_time(d1) / steps,
+            "gemm_ms_alone": gemm_alone_ms,
+            "gemm_ms_beside_decode": g0.elapsed_time(g1) / n_gemm,
+            "gemm_TFLOPs_alone": 2.0 * m ** 3 / (gemm_alone_ms * 1e-3) / 1e12}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +121,10 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="after the timed steps also run 5 plain device copies of BYTES bytes "
                          "(a kernel of known traffic, to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--overlap-gemm", action="store_true",
+                    help="also time the decode steps while a bf16 GEMM loop runs on a second "
+                         "stream of default priority (Section 4.4 of the paper: decode beside "
+                         "the training step's compute), and the GEMM loop alone")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (decode needs no exchange between "
@@ -202,6 +251,9 @@ def main():
                              "frac": algo_bytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                              "algorithmic_bytes_per_launch": algo_bytes}},
     }
+
+    if args.overlap_gemm:
+        result["overlap"] = measure_overlap(torch, step, stream, args.steps, ms_per_step)
 
     if not args.no_cpu_baseline:
         sample = files if args.workload != "imagenet" else files[:128]
