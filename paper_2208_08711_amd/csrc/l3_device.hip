@@ -346,17 +346,15 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
             const uint32_t q = lane + 64 * pass;
             const uint32_t x = word_x[pass];                           /* image column of the word */
             const uint32_t nvalid = word_valid[pass];
-            const uint32_t* src = &parked[buf][c][0][q];
-            const uint32_t pr = src[0], pg = src[QW], pb = src[2 * QW];   /* 4 pixels of R, G, B */
+            const uint32_t* src = &parked[buf][c][0][0];
+            /* interleaved mode: 12 bytes R0 G0 B0 R1 G1 B1 R2 G2 B2 R3 G3 B3 per word q;
+             * planar modes: one word of 4 pixels per channel */
+            const uint32_t pr = MODE == L3_MODE_HWC ? src[3 * q] : src[q];
+            const uint32_t pg = MODE == L3_MODE_HWC ? src[3 * q + 1] : src[QW + q];
+            const uint32_t pb = MODE == L3_MODE_HWC ? src[3 * q + 2] : src[2 * QW + q];
             if (MODE == L3_MODE_HWC) {
                 uint8_t* dst = reinterpret_cast<uint8_t*>((uintptr_t)(out_base + (uint64_t)y * out_row_stride + (uint64_t)x * 3));
-                /* R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3 */
-                const uint32_t t0 = __builtin_amdgcn_perm(pg, pr, 0x010c0400u);
-                const uint32_t o0 = __builtin_amdgcn_perm(pb, t0, 0x03040100u);
-                const uint32_t t1 = __builtin_amdgcn_perm(pb, pg, 0x020c0501u);
-                const uint32_t o1 = __builtin_amdgcn_perm(pr, t1, 0x03060100u);
-                const uint32_t t2 = __builtin_amdgcn_perm(pr, pb, 0x030c0702u);
-                const uint32_t o2 = __builtin_amdgcn_perm(pg, t2, 0x03070100u);
+                const uint32_t o0 = pr, o1 = pg, o2 = pb;
                 if (nvalid == 4) {
                     const u32x3 v = {o0, o1, o2};
                     *reinterpret_cast<global_u32x3_any*>((uintptr_t)dst) = v;
@@ -476,10 +474,24 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
             const uint32_t d3 = __builtin_amdgcn_ubfe(x, w3, w);
             prev[2 * k] = (pred[2 * k] + (d0 | (d2 << 16)) + base2) & 0x00FF00FFu;
             prev[2 * k + 1] = (pred[2 * k + 1] + (d1 | (d3 << 16)) + base2) & 0x00FF00FFu;
-            word[k] = __builtin_amdgcn_perm(prev[2 * k + 1], prev[2 * k], 0x06020400u);   /* p0 p1 p2 p3 */
+            if (MODE != L3_MODE_HWC)
+                word[k] = __builtin_amdgcn_perm(prev[2 * k + 1], prev[2 * k], 0x06020400u);   /* p0 p1 p2 p3 */
         }
+        if (MODE == L3_MODE_HWC) {
+            /* interleave through LDS byte writes (no vector-ALU work): channel c of
+             * pixel i of word k goes to byte 12k + 3i + c of the lane's 12 NW bytes */
+            uint8_t* pb = reinterpret_cast<uint8_t*>(park);
 #pragma unroll
-        for (int k = 0; k < NW; ++k) park[k] = word[k];
+            for (int k = 0; k < NW; ++k) {
+                pb[12 * k + 0] = (uint8_t)prev[2 * k];
+                pb[12 * k + 3] = (uint8_t)prev[2 * k + 1];
+                pb[12 * k + 6] = (uint8_t)(prev[2 * k] >> 16);
+                pb[12 * k + 9] = (uint8_t)(prev[2 * k + 1] >> 16);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < NW; ++k) park[k] = word[k];
+        }
 
         __builtin_amdgcn_sched_barrier(0);
         open_row(hdr_next);
@@ -510,7 +522,12 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
             __syncthreads();
             flush(buf ^ 1u, r - P, P);
         }
-        uint32_t* park = &parked[buf][0][c][lane * NW];
+        /* interleaved mode: this lane's 12 NW bytes of the row, channel c first at byte c;
+         * planar modes: this lane's NW words of channel c */
+        uint32_t* park = MODE == L3_MODE_HWC
+                             ? reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(&parked[buf][0][0][0]) +
+                                                           lane * (12 * NW) + c)
+                             : &parked[buf][0][c][lane * NW];
         do_row(park);
         if (rows > 1) do_row(park + 3 * QW);
         if (rows > 2) {
