@@ -357,7 +357,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                 const uint32_t o0 = pr, o1 = pg, o2 = pb;
                 if (nvalid == 4) {
                     const u32x3 v = {o0, o1, o2};
-                    *reinterpret_cast<global_u32x3_any*>((uintptr_t)dst) = v;
+                    __builtin_nontemporal_store(v, reinterpret_cast<global_u32x3_any*>((uintptr_t)dst));
                 } else if (nvalid) {
                     global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
 #pragma unroll
@@ -372,7 +372,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                     const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
                     uint8_t* dst = reinterpret_cast<uint8_t*>((uintptr_t)(out_base + (uint64_t)ch * out_plane_stride + (uint64_t)y * out_row_stride + x));
                     if (nvalid == 4) {
-                        *reinterpret_cast<global_u32_any*>((uintptr_t)dst) = word;
+                        __builtin_nontemporal_store(word, reinterpret_cast<global_u32_any*>((uintptr_t)dst));
                     } else if (nvalid) {
                         global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
 #pragma unroll
@@ -409,7 +409,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                                 v.x = e0 | (e1 << 16);
                                 v.y = e2 | (e3 << 16);
                             }
-                            *reinterpret_cast<global_u32x2_any*>((uintptr_t)(base + (size_t)col * 2)) = v;
+                            __builtin_nontemporal_store(v, reinterpret_cast<global_u32x2_any*>((uintptr_t)(base + (size_t)col * 2)));
                         } else {
                             global_u16* out16 = reinterpret_cast<global_u16*>((uintptr_t)base);
 #pragma unroll
