@@ -173,6 +173,29 @@ def test_both_lane_widths(l3, ctx, ppl, monkeypatch):
         tensor_case(l3, ctx, [im] * len(crops), crops, 224, 0, patch=patch)
 
 
+def test_large_image_and_odd_output_address(l3, ctx):
+    """A 5760x3840 image (the largest size in the paper's Table "compratio") with the
+    default N = 128, decoded into a buffer that starts at an odd address with an odd
+    row stride; and a 1-row-high, very wide image."""
+    for im in (synth.voronoi_scene(970, 5760, 3840, sites=60), synth.cosine_field(971, 9000, 1)):
+        f = oracle.encode(im)
+        info = l3.peek_header(f)
+        h, w = im.shape[:2]
+        stride = 3 * w + 7
+        dfiles, keep = upload_files([f])
+        raw = torch.full((h * stride + 64,), 0xCD, dtype=torch.uint8, device="cuda")
+        out = raw[3:3 + h * stride]
+        status = torch.ones(1, dtype=torch.int32, device="cuda")
+        l3.decode_batch(ctx, dfiles, [info], [out], status=status, row_strides=[stride])
+        torch.cuda.synchronize()
+        a = raw.cpu().numpy()
+        assert (a[:3] == 0xCD).all() and (a[3 + h * stride:] == 0xCD).all()
+        rows = a[3:3 + h * stride].reshape(h, stride)
+        assert (rows[:, 3 * w:] == 0xCD).all()
+        assert np.array_equal(rows[:, :3 * w].reshape(h, w, 3), im)
+        assert int(status[0]) == 0
+
+
 def test_mixed_patch_sizes_in_one_call(l3, ctx):
     images = [synth.cosine_field(51, 300, 200), synth.cosine_field(52, 300, 200),
               synth.cosine_field(53, 300, 200)]
