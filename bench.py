@@ -30,8 +30,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: plain (non-packed-rate) vector ALU lane-operations
 VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# VALU instructions of the steady-state row per lane (52) over the 4 bytes the lane decodes
-ALGORITHMIC_LANE_OPS_PER_DECODED_BYTE = 52 / 4
+# VALU instructions of the steady-state row per lane (51) over the 4 bytes the lane decodes
+ALGORITHMIC_LANE_OPS_PER_DECODED_BYTE = 51 / 4
 
 
 def read_traffic(workload):
