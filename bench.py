@@ -121,6 +121,9 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="after the timed steps also run 5 plain device copies of BYTES bytes "
                          "(a kernel of known traffic, to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--patch", type=int, default=0,
+                    help="encode the workload with this patch size instead of the paper's rule "
+                         "(32, 64 or 128; for the patch-size sweep)")
     ap.add_argument("--overlap-gemm", action="store_true",
                     help="also time the decode steps while a bf16 GEMM loop runs on a second "
                          "stream of default priority (Section 4.4 of the paper: decode beside "
@@ -141,7 +144,9 @@ def main():
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
     images, label = make_workload(args.workload)
     with ThreadPoolExecutor(cores) as pool:
-        files = list(pool.map(oracle.encode, images))
+        files = list(pool.map(lambda im: oracle.encode(im, args.patch), images))
+    if args.patch:
+        label += " [patch size forced to %d]" % args.patch
     n = len(files)
     file_bytes = sum(len(f) for f in files)
     decoded_bytes = sum(im.size for im in images)

@@ -170,6 +170,33 @@ l3_status l3_decode_crop_normalize_batch(l3_ctx* ctx, const l3_item* items,
                                          l3_dtype dtype, void* d_out_nchw,
                                          uint32_t* d_status, void* stream);
 
+typedef struct {
+    const uint8_t* d_rgb;      /* DEVICE: interleaved 8-bit RGB, rows row_stride bytes apart */
+    size_t         row_stride; /* >= 3 * width */
+    uint32_t       width, height;
+    uint8_t        patch;      /* N, 1..128; 0 = l3_default_patch */
+    uint8_t*       d_file;     /* DEVICE: receives the L3 file */
+    size_t         file_cap;   /* its capacity in bytes (l3_encode_bound is always enough) */
+} l3_encode_item;
+
+/* Section 4.2 (encoding direction) + Section 4.3 on the GPU: encode n images held
+ * in device memory into n L3 files in device memory.  The files are byte for byte
+ * the ones l3_encode_cpu writes for the same pixels and patch size.
+ *   items       HOST array of n entries (copied before return).
+ *   d_file_len  DEVICE array of n u64: entry i receives the length of file i (the
+ *               length it needs, if the capacity was too small).
+ *   d_status    DEVICE array of n u32, or NULL: 0 = file written; bit 0 = file_cap
+ *               too small (header and offsets are written if they fit, no patch
+ *               data; nothing is written beyond file_cap); bit 1 = encoded data
+ *               beyond 4 GiB (not representable in the format's 32-bit offsets).
+ *   stream      a hipStream_t; the call returns after enqueueing.  Calls on one
+ *               context reuse one workspace: a second call waits (on the host) for
+ *               the kernels of the first.
+ * Patch sizes above 128 give UNSUPPORTED.  Errors are synchronous: INVALID_ARG,
+ * UNSUPPORTED, DEVICE (a HIP call failed; some kernels may have been enqueued). */
+l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, int n,
+                          uint64_t* d_file_len, uint32_t* d_status, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

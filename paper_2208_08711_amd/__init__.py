@@ -6,6 +6,6 @@ built into libl3.so next to this file).  This package only marshals arguments.
 from .binding import (  # noqa: F401
     L3Error, Context, Info, default_patch, encode_bound, encode_cpu, peek_header,
     decode_batch, decode_crop_normalize_batch, PreparedBatch, decode_batch_prepared,
-    PreparedCropBatch, decode_crop_normalize_batch_prepared, library_path, status_string,
+    PreparedCropBatch, decode_crop_normalize_batch_prepared, encode_batch, library_path, status_string,
     LAYOUT_HWC, LAYOUT_CHW, BF16, FP16, EXPORTED_SYMBOLS,
 )

@@ -19,6 +19,7 @@ BF16, FP16 = 0, 1
 EXPORTED_SYMBOLS = (
     "l3_status_string", "l3_default_patch", "l3_encode_bound", "l3_encode_cpu", "l3_peek_header",
     "l3_ctx_create", "l3_ctx_destroy", "l3_decode_batch", "l3_decode_crop_normalize_batch",
+    "l3_encode_batch",
 )
 
 
@@ -37,6 +38,12 @@ class Info(ctypes.Structure):
 class _Item(ctypes.Structure):
     _fields_ = [("d_file", ctypes.c_void_p), ("file_len", ctypes.c_size_t), ("info", Info),
                 ("d_out", ctypes.c_void_p), ("out_row_stride", ctypes.c_size_t)]
+
+
+class _EncodeItem(ctypes.Structure):
+    _fields_ = [("d_rgb", ctypes.c_void_p), ("row_stride", ctypes.c_size_t),
+                ("width", ctypes.c_uint32), ("height", ctypes.c_uint32), ("patch", ctypes.c_uint8),
+                ("d_file", ctypes.c_void_p), ("file_cap", ctypes.c_size_t)]
 
 
 class _Crop(ctypes.Structure):
@@ -85,6 +92,9 @@ def _load():
         ctypes.c_uint32, ctypes.c_uint32, ctypes.POINTER(ctypes.c_float),
         ctypes.POINTER(ctypes.c_float), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_void_p]
+    lib.l3_encode_batch.restype = ctypes.c_int
+    lib.l3_encode_batch.argtypes = [ctypes.c_void_p, ctypes.POINTER(_EncodeItem), ctypes.c_int,
+                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     _lib = lib
     return lib
 
@@ -253,3 +263,22 @@ def decode_crop_normalize_batch_prepared(ctx, batch, crop_w, crop_h, out, dtype=
         ctypes.c_void_p(out.data_ptr()),
         ctypes.c_void_p(status.data_ptr() if status is not None else None), _stream_ptr(stream)),
         "l3_decode_crop_normalize_batch")
+
+
+def encode_batch(ctx, images, files, file_len, patch=0, status=None, stream=None, row_strides=None):
+    """images: list of uint8 device tensors [H, W, 3] (rows contiguous unless row_strides is
+    given); files: list of uint8 device tensors that receive the L3 files; file_len: int64 (or
+    uint64) device tensor of len(images) words; patch: one N for all or a list."""
+    n = len(images)
+    arr = (_EncodeItem * max(n, 1))()
+    for i in range(n):
+        h, w = int(images[i].shape[0]), int(images[i].shape[1])
+        arr[i].d_rgb = images[i].data_ptr()
+        arr[i].row_stride = row_strides[i] if row_strides is not None else 3 * w
+        arr[i].width, arr[i].height = w, h
+        arr[i].patch = patch[i] if isinstance(patch, (list, tuple)) else patch
+        arr[i].d_file = files[i].data_ptr()
+        arr[i].file_cap = files[i].numel()
+    _check(_load().l3_encode_batch(ctx.handle, arr, n, ctypes.c_void_p(file_len.data_ptr()),
+                                   ctypes.c_void_p(status.data_ptr() if status is not None else None),
+                                   _stream_ptr(stream)), "l3_encode_batch")

@@ -12,7 +12,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libl3.so")
-SOURCES = [os.path.join(CSRC, "l3_host.cpp"), os.path.join(CSRC, "l3_device.hip")]
+SOURCES = [os.path.join(CSRC, "l3_host.cpp"), os.path.join(CSRC, "l3_device.hip"),
+           os.path.join(CSRC, "l3_encode.hip")]
 
 
 def build(verbose: bool = False) -> str:

@@ -1,0 +1,45 @@
+/*
+ * The context object behind the opaque l3_ctx of include/l3.h, shared by the
+ * translation units that enqueue GPU work.  Not part of the public ABI.
+ */
+#ifndef L3_CTX_H
+#define L3_CTX_H
+
+#include <hip/hip_runtime.h>
+
+#include "l3_internal.h"
+
+constexpr int kSlots = 4;   /* descriptor staging slots: calls in flight before the host waits */
+
+struct L3EncodeState;                          /* workspace of l3_encode_batch, owned by its file */
+void l3_encode_state_free(L3EncodeState* s);   /* NULL allowed */
+
+struct l3_ctx {
+    int device = 0;
+    L3ImageDesc* scratch = nullptr;       /* host: descriptors of the call being planned */
+    size_t scratch_cap = 0;
+    size_t cap = 0;                       /* descriptors per slot */
+    L3ImageDesc* h_stage[kSlots] = {};    /* pinned host */
+    L3ImageDesc* d_descs[kSlots] = {};    /* device */
+    uint16_t* d_table[kSlots] = {};       /* device: 768-entry normalisation table */
+    hipEvent_t done[kSlots] = {};         /* the slot's kernels have finished */
+    bool pending[kSlots] = {};
+    int next = 0;
+    L3EncodeState* enc = nullptr;
+};
+
+/* Makes the context's device current for the lifetime of the guard. */
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int device) {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        ok = prev == device || hipSetDevice(device) == hipSuccess;
+    }
+    ~DeviceGuard() {
+        int now = -1;
+        if (prev >= 0 && hipGetDevice(&now) == hipSuccess && now != prev) (void)hipSetDevice(prev);
+    }
+};
+
+#endif

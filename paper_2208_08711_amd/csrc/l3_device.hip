@@ -39,6 +39,7 @@
 #include <new>
 
 #include "l3_internal.h"
+#include "l3_ctx.h"
 
 namespace {
 
@@ -629,7 +630,6 @@ __global__ void l3_prepare_kernel(const uint64_t* __restrict__ pinned_src, uint6
 
 /* ---- host side: context, planning, launch ------------------------------- */
 
-constexpr int kSlots = 4;   /* descriptor staging slots: calls in flight before the host waits */
 
 typedef void (*decode_kernel_t)(const L3ImageDesc*, uint32_t*, uint32_t, uint32_t, const uint16_t*);
 typedef void (*decode_kernel_args_t)(const DescPack, uint32_t*, uint32_t, uint32_t, const uint16_t*);
@@ -685,19 +685,6 @@ KernelChoice pick_kernel(int n, int mode) {
 
 }  // namespace
 
-struct l3_ctx {
-    int device = 0;
-    L3ImageDesc* scratch = nullptr;       /* host: descriptors of the call being planned */
-    size_t scratch_cap = 0;
-    size_t cap = 0;                       /* descriptors per slot */
-    L3ImageDesc* h_stage[kSlots] = {};    /* pinned host */
-    L3ImageDesc* d_descs[kSlots] = {};    /* device */
-    uint16_t* d_table[kSlots] = {};       /* device: 768-entry normalisation table */
-    hipEvent_t done[kSlots] = {};         /* the slot's kernels have finished */
-    bool pending[kSlots] = {};
-    int next = 0;
-};
-
 namespace {
 
 void release_slots(l3_ctx* ctx) {
@@ -732,19 +719,6 @@ l3_status ensure_capacity(l3_ctx* ctx, size_t n) {
     ctx->cap = cap;
     return L3_OK;
 }
-
-struct DeviceGuard {
-    int prev = -1;
-    bool ok = false;
-    explicit DeviceGuard(int device) {
-        if (hipGetDevice(&prev) != hipSuccess) return;
-        ok = prev == device || hipSetDevice(device) == hipSuccess;
-    }
-    ~DeviceGuard() {
-        int now = -1;
-        if (prev >= 0 && hipGetDevice(&now) == hipSuccess && now != prev) (void)hipSetDevice(prev);
-    }
-};
 
 /* Checks one item against what the GPU path needs; fills the mode-independent
  * part of its descriptor. */
@@ -944,6 +918,7 @@ void l3_ctx_destroy(l3_ctx* ctx) {
     }
     release_slots(ctx);
     std::free(ctx->scratch);
+    l3_encode_state_free(ctx->enc);
     delete ctx;
 }
 

@@ -1,0 +1,166 @@
+"""GPU encoder parity: l3_encode_batch must write, byte for byte, the file the CPU oracle
+writes for the same pixels (arxiv 2208.08711 Section 4.2 encoding direction, Section 4.3)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2208_08711_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def l3():
+    import paper_2208_08711_amd as mod
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return mod
+
+
+@pytest.fixture(scope="module")
+def ctx(l3):
+    c = l3.Context(0)
+    yield c
+    c.close()
+
+
+def gpu_encode(l3, ctx, images, patch=0, slack=0, pad_cols=0):
+    dimgs, strides = [], []
+    for im in images:
+        h, w = im.shape[:2]
+        stride = 3 * w + pad_cols
+        host = np.full((h, stride), 0xEE, dtype=np.uint8)
+        host[:, :3 * w] = im.reshape(h, 3 * w)
+        dimgs.append(torch.from_numpy(host).cuda())
+        strides.append(stride)
+    caps = [l3.encode_bound(im.shape[1], im.shape[0],
+                            patch[i] if isinstance(patch, list) else patch) + slack
+            for i, im in enumerate(images)]
+    files = [torch.full((cap + 16,), 0xAB, dtype=torch.uint8, device="cuda") for cap in caps]
+    views = [f[:cap] for f, cap in zip(files, caps)]
+    lens = torch.zeros(len(images), dtype=torch.int64, device="cuda")
+    status = torch.full((len(images),), 7, dtype=torch.int32, device="cuda")
+    l3.encode_batch(ctx, [_as_hw3(d, im) for d, im in zip(dimgs, images)], views, lens, patch=patch,
+                    status=status, row_strides=strides)
+    torch.cuda.synchronize()
+    out = []
+    for f, cap, n in zip(files, caps, lens.cpu().tolist()):
+        a = f.cpu().numpy()
+        assert (a[max(n, 0):] == 0xAB).all() or n > cap, "wrote beyond the file"
+        out.append(a[:n].tobytes())
+    return out, status.cpu().numpy()
+
+
+class _Shape:
+    """Just enough of a tensor for the binding: data_ptr and shape."""
+
+    def __init__(self, t, h, w):
+        self._t, self.shape = t, (h, w, 3)
+
+    def data_ptr(self):
+        return self._t.data_ptr()
+
+
+def _as_hw3(d, im):
+    return _Shape(d, im.shape[0], im.shape[1])
+
+
+def check(l3, ctx, images, patch=0, pad_cols=0):
+    got, status = gpu_encode(l3, ctx, images, patch=patch, pad_cols=pad_cols)
+    assert (status == 0).all(), status
+    for k, (g, im) in enumerate(zip(got, images)):
+        p = patch[k] if isinstance(patch, list) else patch
+        want = oracle.encode(im, p)
+        assert len(g) == len(want), (k, im.shape, p, len(g), len(want))
+        assert g == want, (k, im.shape, p)
+        assert np.array_equal(oracle.decode(g), im)
+
+
+def test_config1_and_handmade(l3, ctx):
+    check(l3, ctx, synth.config1())
+    img = np.zeros((2, 3, 3), dtype=np.uint8)
+    img[0, :, 0] = [65, 70, 72]
+    img[1, :, 0] = [66, 74, 71]
+    img[:, :, 1] = 200
+    img[0, :, 2] = 10
+    img[1, :, 2] = 13
+    check(l3, ctx, [img], patch=3)
+
+
+EDGE = [(1, 1), (2, 1), (1, 2), (3, 5), (5, 3), (31, 33), (33, 31), (63, 65), (65, 63), (127, 3),
+        (129, 127), (130, 129), (257, 40), (40, 257), (450, 337)]
+
+
+@pytest.mark.parametrize("patch", [1, 3, 32, 64, 100, 128])
+def test_edge_shapes_and_patch_sizes(l3, ctx, patch):
+    images = []
+    for k, (w, h) in enumerate(EDGE):
+        if patch <= 3 and w * h > 3000:
+            continue
+        images.append(synth.cosine_field(1700 + k, w, h))
+        images.append(synth.uniform_bytes(1800 + k, w, h))
+    check(l3, ctx, images, patch=patch, pad_cols=5)
+
+
+def test_degenerate_content(l3, ctx):
+    h, w = 70, 150
+    yy, xx = np.mgrid[0:h, 0:w]
+    images = [np.zeros((h, w, 3), np.uint8), np.full((h, w, 3), 255, np.uint8),
+              (((yy + xx) & 1) * 255).astype(np.uint8)[:, :, None].repeat(3, 2),
+              ((yy & 1) * 255).astype(np.uint8)[:, :, None].repeat(3, 2),
+              (xx * 3 % 256).astype(np.uint8)[:, :, None].repeat(3, 2),
+              (yy * 5 % 256).astype(np.uint8)[:, :, None].repeat(3, 2)]
+    for patch in (32, 128):
+        check(l3, ctx, images, patch=patch)
+
+
+def test_benchmark_configurations(l3, ctx):
+    """Default patch rule on the benchmark shapes: a slice of the photo-sized batch, two
+    street-scene images, one compressible and one incompressible 3840x2160 image."""
+    check(l3, ctx, synth.config2(12))
+    check(l3, ctx, synth.config3(2))
+    check(l3, ctx, [synth.gradient_noise(4000, 3840, 2160, 2.0, span=255.0),
+                    synth.uniform_bytes(4004, 3840, 2160)])
+
+
+def test_mixed_patch_sizes_and_round_trip_through_the_gpu_decoder(l3, ctx):
+    images = [synth.cosine_field(1900 + k, 300, 200) for k in range(3)]
+    patches = [128, 32, 64]
+    got, status = gpu_encode(l3, ctx, images, patch=patches)
+    assert (status == 0).all()
+    infos = [l3.peek_header(g) for g in got]
+    dfiles = [torch.from_numpy(np.frombuffer(g, dtype=np.uint8).copy()).cuda() for g in got]
+    outs = [torch.zeros(im.shape, dtype=torch.uint8, device="cuda") for im in images]
+    l3.decode_batch(ctx, dfiles, infos, outs)
+    torch.cuda.synchronize()
+    for o, im in zip(outs, images):
+        assert np.array_equal(o.cpu().numpy(), im)
+
+
+def test_capacity_too_small_is_reported_and_contained(l3, ctx):
+    im = synth.cosine_field(1950, 200, 120)
+    want = oracle.encode(im, 32)
+    d = torch.from_numpy(im.reshape(120, 600).copy()).cuda()
+    for cap in (len(want) - 1, 13 + 12 * 28 + 5, 20, 1):
+        buf = torch.full((len(want) + 64,), 0xAB, dtype=torch.uint8, device="cuda")
+        lens = torch.zeros(1, dtype=torch.int64, device="cuda")
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        l3.encode_batch(ctx, [_Shape(d, 120, 200)], [buf[:cap]], lens, patch=32, status=status)
+        torch.cuda.synchronize()
+        assert int(status[0]) & 1
+        assert int(lens[0]) == len(want)                       # the length it needs
+        assert (buf.cpu().numpy()[cap:] == 0xAB).all()         # nothing beyond the capacity
+
+
+def test_host_errors(l3, ctx):
+    im = synth.cosine_field(1960, 300, 200)
+    d = torch.from_numpy(im.reshape(200, 900).copy()).cuda()
+    buf = torch.zeros(l3.encode_bound(300, 200, 200), dtype=torch.uint8, device="cuda")
+    lens = torch.zeros(1, dtype=torch.int64, device="cuda")
+    with pytest.raises(l3.L3Error) as e:
+        l3.encode_batch(ctx, [_Shape(d, 200, 300)], [buf], lens, patch=200)     # N > 128
+    assert e.value.code == 6
+    with pytest.raises(l3.L3Error) as e:
+        l3.encode_batch(ctx, [_Shape(d, 200, 300)], [buf], lens, patch=32, row_strides=[899])
+    assert e.value.code == 1
