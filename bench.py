@@ -65,6 +65,38 @@ def make_workload(name):
     raise SystemExit(f"unknown workload {name}")
 
 
+def measure_encode(torch, l3, ctx, images, files, stream, patch):
+    """l3_encode_batch on the workload's images; the files must equal the oracle's."""
+    n = len(images)
+    dimgs = [torch.from_numpy(np.ascontiguousarray(im)).cuda() for im in images]
+    caps = [l3.encode_bound(im.shape[1], im.shape[0], patch) for im in images]
+    dfiles = [torch.empty(c, dtype=torch.uint8, device="cuda") for c in caps]
+    lens = torch.zeros(n, dtype=torch.int64, device="cuda")
+    status = torch.zeros(n, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        l3.encode_batch(ctx, dimgs, dfiles, lens, patch=patch, status=status, stream=stream)
+    torch.cuda.synchronize()
+    reps = 20
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(reps):
+        l3.encode_batch(ctx, dimgs, dfiles, lens, patch=patch, status=status, stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    if int(status.abs().sum()) != 0:
+        raise SystemExit("bench.py: encoder reported a status")
+    got = lens.cpu().tolist()
+    for i in (0, n // 2, n - 1):
+        if dfiles[i][:got[i]].cpu().numpy().tobytes() != files[i]:
+            raise SystemExit("bench.py: GPU-encoded file differs from the oracle's")
+    raw = sum(im.size for im in images)
+    out = sum(got)
+    return {"ms_per_batch": ms, "images_per_s": n / (ms * 1e-3), "raw_GBps": raw / (ms * 1e-3) / 1e9,
+            "hbm_fraction": (raw + out) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "note": "three kernels per call (measure, layout, pack); the pixels are read twice"}
+
+
 def measure_overlap(torch, step, stream, steps, decode_alone_ms):
     """Decode steps on `stream`, a bf16 GEMM loop on a second stream (both default
     priority): each alone and both together."""
@@ -124,6 +156,9 @@ def main():
     ap.add_argument("--patch", type=int, default=0,
                     help="encode the workload with this patch size instead of the paper's rule "
                          "(32, 64 or 128; for the patch-size sweep)")
+    ap.add_argument("--encode", action="store_true",
+                    help="also time l3_encode_batch on the same images (pixels resident in HBM) "
+                         "and check its files against the oracle's")
     ap.add_argument("--overlap-gemm", action="store_true",
                     help="also time the decode steps while a bf16 GEMM loop runs on a second "
                          "stream of default priority (Section 4.4 of the paper: decode beside "
@@ -259,6 +294,8 @@ def main():
 
     if args.overlap_gemm:
         result["overlap"] = measure_overlap(torch, step, stream, args.steps, ms_per_step)
+    if args.encode:
+        result["encode"] = measure_encode(torch, l3, ctx, images, files, stream, args.patch)
 
     if not args.no_cpu_baseline:
         sample = files if args.workload != "imagenet" else files[:128]

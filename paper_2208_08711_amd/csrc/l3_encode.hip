@@ -31,7 +31,6 @@
 namespace {
 
 constexpr int kMaxPatch = 128;                       /* two pixels per lane */
-constexpr int kPatchWordsMax = (kMaxPatch * (12 + 8 * kMaxPatch) + 31) / 32 + 2;
 
 struct L3EncodeDesc {
     const uint8_t* rgb;
@@ -81,10 +80,15 @@ __device__ uint32_t walk_patch(const L3EncodeDesc& d, uint32_t c, uint32_t tx, u
 
     int up0 = 0, up1 = 0;           /* the original row above */
     uint32_t pos = 0;               /* bit position of the current row's record */
+    int next0 = has0 ? src[3 * (size_t)lane] : 0;             /* the row after, already travelling */
+    int next1 = has1 ? src[3 * (size_t)(lane + 64)] : 0;
     for (uint32_t r = 0; r < ph; ++r) {
-        const uint8_t* row = src + (size_t)r * d.row_stride;
-        const int cur0 = has0 ? row[3 * (size_t)lane] : 0;
-        const int cur1 = has1 ? row[3 * (size_t)(lane + 64)] : 0;
+        const int cur0 = next0, cur1 = next1;
+        if (r + 1 < ph) {
+            const uint8_t* row = src + (size_t)(r + 1) * d.row_stride;
+            next0 = has0 ? row[3 * (size_t)lane] : 0;
+            next1 = has1 ? row[3 * (size_t)(lane + 64)] : 0;
+        }
         int v0, v1;
         if (r == 0) {
             v0 = cur0;              /* first row raw, taken as unsigned */
@@ -211,7 +215,7 @@ __global__ __launch_bounds__(64) void l3_encode_pack_kernel(const L3EncodeDesc* 
     const uint64_t need = file_len[d.status_index];
     if (need > d.file_cap || need - (13 + 12ull * patches) > 0xFFFFFFFFull) return;
 
-    __shared__ uint32_t bits[kPatchWordsMax];
+    extern __shared__ uint32_t bits[];   /* sized by the host for the largest patch of the launch */
     const uint32_t bytes = sizes[d.sizes_base + k];
     const uint32_t words = (bytes + 3) / 4 + 1;
     for (uint32_t i = threadIdx.x; i < words; i += 64) bits[i] = 0;
@@ -261,7 +265,7 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
     if (!guard.ok) return L3_ERR_DEVICE;
 
     size_t total_patches = 0;
-    uint32_t max_patches = 0;
+    uint32_t max_patches = 0, max_n = 1;
     for (int i = 0; i < n; ++i) {
         const l3_encode_item& it = items[i];
         if (!it.d_rgb || !it.d_file || it.width == 0 || it.height == 0 ||
@@ -269,6 +273,7 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
             return L3_ERR_INVALID_ARG;
         const uint32_t np = it.patch ? it.patch : l3_default_patch(it.width, it.height);
         if (np > kMaxPatch) return L3_ERR_UNSUPPORTED;
+        if (np > max_n) max_n = np;
         if (it.width > (1u << 24) || it.height > (1u << 24)) return L3_ERR_UNSUPPORTED;
         const uint64_t p = (uint64_t)((it.width + np - 1) / np) * ((it.height + np - 1) / np);
         if (3 * p > 0x7FFFFFFFull) return L3_ERR_UNSUPPORTED;
@@ -341,10 +346,11 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
     }
     hipLaunchKernelGGL(l3_encode_layout_kernel, dim3((uint32_t)n), dim3(256), 0, stream, st->d_descs,
                        st->d_sizes, d_file_len, d_status);
+    const size_t lds_bytes = ((size_t)max_n * (12 + 8 * (size_t)max_n) + 31) / 32 * 4 + 8;
     for (int first = 0; first < n; first += 65535) {
         const int m = n - first < 65535 ? n - first : 65535;
-        hipLaunchKernelGGL(l3_encode_pack_kernel, dim3(max_patches, (uint32_t)m), dim3(64), 0, stream,
-                           st->d_descs + first, st->d_sizes, d_file_len);
+        hipLaunchKernelGGL(l3_encode_pack_kernel, dim3(max_patches, (uint32_t)m), dim3(64), lds_bytes,
+                           stream, st->d_descs + first, st->d_sizes, d_file_len);
     }
     if (hipGetLastError() != hipSuccess) return L3_ERR_DEVICE;
     if (hipEventRecord(st->done, stream) != hipSuccess) return L3_ERR_DEVICE;
