@@ -65,6 +65,56 @@ def make_workload(name):
     raise SystemExit(f"unknown workload {name}")
 
 
+def measure_load_decode(torch, l3, ctx, images, files, infos, stream):
+    """Host-resident files -> H2D copy on a side stream -> decode, two buffer sets."""
+    n = len(files)
+    offs, pos = [], 0
+    for f in files:
+        offs.append(pos)
+        pos = (pos + len(f) + 63) // 64 * 64
+    blob = torch.empty(pos, dtype=torch.uint8, pin_memory=True)
+    hb = blob.numpy()
+    for o, f in zip(offs, files):
+        hb[o:o + len(f)] = np.frombuffer(f, dtype=np.uint8)
+    copy_stream = torch.cuda.Stream()
+    sets = []
+    for _ in range(2):
+        dev = torch.empty(pos, dtype=torch.uint8, device="cuda")
+        dfiles = [dev[o:o + len(f)] for o, f in zip(offs, files)]
+        outs = [torch.empty((im.shape[0], im.shape[1] * 3), dtype=torch.uint8, device="cuda")
+                for im in images]
+        sets.append({"dev": dev, "batch": l3.PreparedBatch(dfiles, infos, outs), "outs": outs,
+                     "copied": torch.cuda.Event(), "decoded": torch.cuda.Event()})
+
+    def run(steps):
+        for k in range(steps):
+            s = sets[k % 2]
+            copy_stream.wait_event(s["decoded"])          # the set's previous decode has read it
+            with torch.cuda.stream(copy_stream):
+                s["dev"].copy_(blob, non_blocking=True)
+                s["copied"].record(copy_stream)
+            stream.wait_event(s["copied"])
+            l3.decode_batch_prepared(ctx, s["batch"], stream=stream)
+            s["decoded"].record(stream)
+
+    for s in sets:
+        s["decoded"].record(stream)
+    run(4)
+    torch.cuda.synchronize()
+    steps = 40
+    t0 = time.perf_counter()
+    run(steps)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    for t, im in zip(sets[(steps - 1) % 2]["outs"], images):
+        if not np.array_equal(t.cpu().numpy().reshape(im.shape), im):
+            raise SystemExit("bench.py: pipeline output differs from the input images")
+    return {"ms_per_batch": dt * 1e3, "images_per_s": n / dt, "file_bytes_per_batch": sum(map(len, files)),
+            "h2d_GBps": pos / dt / 1e9,
+            "note": "files in pinned host memory, one H2D copy per batch on a second stream, "
+                    "double-buffered against the decode"}
+
+
 def measure_encode(torch, l3, ctx, images, files, stream, patch):
     """l3_encode_batch on the workload's images; the files must equal l3_encode_cpu's."""
     n = len(images)
@@ -156,6 +206,10 @@ def main():
     ap.add_argument("--patch", type=int, default=0,
                     help="encode the workload with this patch size instead of the paper's rule "
                          "(32, 64 or 128; for the patch-size sweep)")
+    ap.add_argument("--load-pipeline", action="store_true",
+                    help="also time Load+Decode: the files start in pinned host memory, are copied "
+                         "to the GPU on a second stream and decoded, double-buffered (the paper's "
+                         "data-preparation measurement, Section 5.3, with host RAM as the source)")
     ap.add_argument("--encode", action="store_true",
                     help="also time l3_encode_batch on the same images (pixels resident in HBM) "
                          "and check its files against l3_encode_cpu's")
@@ -299,6 +353,8 @@ def main():
 
     if args.overlap_gemm:
         result["overlap"] = measure_overlap(torch, step, stream, args.steps, ms_per_step)
+    if args.load_pipeline and not fused:
+        result["load_decode"] = measure_load_decode(torch, l3, ctx, images, files, infos, stream)
     if args.encode:
         result["encode"] = measure_encode(torch, l3, ctx, images, files, stream, args.patch)
 
