@@ -54,6 +54,19 @@ def _load():
     lib.l3o_encode.argtypes = [u8p, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_size_t,
                                ctypes.c_uint32, ctypes.c_int, u8p, ctypes.c_size_t,
                                ctypes.POINTER(ctypes.c_size_t)]
+    lib.l3o_encode_with.restype = ctypes.c_int
+    lib.l3o_encode_with.argtypes = [u8p, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_size_t,
+                                    ctypes.c_uint32, ctypes.c_int, ctypes.c_int, u8p,
+                                    ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+    lib.l3o_decode_with.restype = ctypes.c_int
+    lib.l3o_decode_with.argtypes = [u8p, ctypes.c_size_t, ctypes.c_int, u8p, ctypes.c_size_t]
+    lib.l3o_decode_patch_with.restype = ctypes.c_int
+    lib.l3o_decode_patch_with.argtypes = [u8p, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_uint32,
+                                          ctypes.c_int, u8p, ctypes.c_size_t]
+    lib.l3o_predict_original.restype = ctypes.c_uint8
+    lib.l3o_predict_original.argtypes = [ctypes.c_uint8] * 3
+    lib.l3o_predict_original_batch.restype = None
+    lib.l3o_predict_original_batch.argtypes = [u8p, u8p, u8p, u8p, ctypes.c_size_t]
     lib.l3o_parse_header.restype = ctypes.c_int
     lib.l3o_parse_header.argtypes = [u8p, ctypes.c_size_t, ctypes.POINTER(_Info)]
     lib.l3o_decode.restype = ctypes.c_int
@@ -101,7 +114,18 @@ def predict_batch(tl, t, tr):
     return out
 
 
-def encode(rgb, patch=0, width_mode=0):
+PREDICTOR_CUSTOM, PREDICTOR_ORIGINAL = 0, 1
+
+
+def predict_original_batch(left, top, top_left):
+    left, top, top_left = (np.ascontiguousarray(v, dtype=np.uint8).ravel()
+                           for v in (left, top, top_left))
+    out = np.empty_like(top)
+    _load().l3o_predict_original_batch(_u8(left), _u8(top), _u8(top_left), _u8(out), top.size)
+    return out
+
+
+def encode(rgb, patch=0, width_mode=0, predictor=PREDICTOR_CUSTOM):
     """rgb: uint8 array [H, W, 3] (rows may be strided).  Returns bytes."""
     rgb = np.asarray(rgb)
     assert rgb.dtype == np.uint8 and rgb.ndim == 3 and rgb.shape[2] == 3
@@ -112,8 +136,8 @@ def encode(rgb, patch=0, width_mode=0):
     cap = lib.l3o_encode_bound(w, h, patch)
     out = np.empty(cap, dtype=np.uint8)
     n = ctypes.c_size_t(0)
-    rc = lib.l3o_encode(_u8(rgb), w, h, rgb.strides[0], patch, width_mode, _u8(out), cap,
-                        ctypes.byref(n))
+    rc = lib.l3o_encode_with(_u8(rgb), w, h, rgb.strides[0], patch, width_mode, predictor,
+                             _u8(out), cap, ctypes.byref(n))
     if rc != OK:
         raise OracleError(rc, "encode")
     return out[:n.value].tobytes()
@@ -128,13 +152,13 @@ def parse_header(file):
     return {k: int(getattr(info, k)) for k, _ in _Info._fields_}
 
 
-def decode(file, row_stride=None):
+def decode(file, row_stride=None, predictor=PREDICTOR_CUSTOM):
     a = _bytes_arr(file)
     info = parse_header(a)
     w, h = info["width"], info["height"]
     stride = row_stride or 3 * w
     out = np.zeros((h, stride), dtype=np.uint8)
-    rc = _load().l3o_decode(_u8(a), a.size, _u8(out), stride)
+    rc = _load().l3o_decode_with(_u8(a), a.size, predictor, _u8(out), stride)
     if rc != OK:
         raise OracleError(rc, "decode")
     return out[:, :3 * w].reshape(h, w, 3)
@@ -150,10 +174,10 @@ def decode_residuals(file):
     return out
 
 
-def decode_patch(stream, pw, ph):
+def decode_patch(stream, pw, ph, predictor=PREDICTOR_CUSTOM):
     a = _bytes_arr(stream)
     out = np.zeros((ph, pw), dtype=np.uint8)
-    rc = _load().l3o_decode_patch(_u8(a), a.size, pw, ph, _u8(out), pw)
+    rc = _load().l3o_decode_patch_with(_u8(a), a.size, pw, ph, predictor, _u8(out), pw)
     if rc != OK:
         raise OracleError(rc, "decode_patch")
     return out

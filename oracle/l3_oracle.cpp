@@ -80,6 +80,29 @@ int predict_at(const uint8_t* above, uint32_t x, uint32_t pw) {
     return predict_int(above[x - 1], above[x], above[x + 1]);
 }
 
+/* Section 4.2, first paragraph of "Custom Paeth Filter": the original Paeth
+ * filter, which looks at left, top and top-left.  Reference value
+ * left + top - top_left, nearest of the three wins, ties in the order left,
+ * top, top-left (the order PNG's filter type 4 uses). */
+int predict_original_int(int left, int top, int top_left) {
+    int ref = left + top - top_left;
+    int d_left = std::abs(ref - left);
+    int d_top = std::abs(ref - top);
+    int d_tl = std::abs(ref - top_left);
+    if (d_left <= d_top && d_left <= d_tl) return left;
+    if (d_top <= d_tl) return top;
+    return top_left;
+}
+
+/* The original predictor at column x of a row (rows >= 1), from the row above
+ * and the pixels of the current row to the left.  In the first column there is
+ * no left and no top-left pixel: the prediction is "top" (which is also what
+ * the rule above gives when the two missing pixels count as 0). */
+int predict_original_at(const uint8_t* above, const uint8_t* cur, uint32_t x) {
+    if (x == 0) return above[0];
+    return predict_original_int(cur[x - 1], above[x], above[x - 1]);
+}
+
 unsigned bit_length(unsigned v) {
     unsigned n = 0;
     while (v) { ++n; v >>= 1; }
@@ -89,13 +112,15 @@ unsigned bit_length(unsigned v) {
 /* Encode one pw x ph patch of one channel (pixels at src, rows src_stride
  * apart, pixel_step bytes between pixels of a row) onto the bit writer. */
 void encode_patch(const uint8_t* src, size_t src_stride, size_t pixel_step,
-                  uint32_t pw, uint32_t ph, int width_mode, BitWriter& bw) {
+                  uint32_t pw, uint32_t ph, int width_mode, int predictor, BitWriter& bw) {
     std::vector<uint8_t> above(pw), cur(pw), resid(pw);
     for (uint32_t r = 0; r < ph; ++r) {
         for (uint32_t x = 0; x < pw; ++x) cur[x] = src[r * src_stride + x * pixel_step];
         /* stage 1: filter (first row skipped: kept raw) */
         for (uint32_t x = 0; x < pw; ++x) {
             if (r == 0) resid[x] = cur[x];
+            else if (predictor == L3O_PREDICTOR_ORIGINAL)
+                resid[x] = (uint8_t)(cur[x] - predict_original_at(above.data(), cur.data(), x));
             else resid[x] = (uint8_t)(cur[x] - predict_at(above.data(), x, pw));
         }
         /* stage 2: base-delta, steps 1-4 */
@@ -141,12 +166,14 @@ int unpack_patch(const uint8_t* stream, size_t len, uint32_t pw, uint32_t ph,
 
 /* Inverse filter over a residual plane, in place row by row into out. */
 void unfilter_patch(const uint8_t* resid, size_t rstride, uint32_t pw, uint32_t ph,
-                    uint8_t* out, size_t ostride) {
+                    int predictor, uint8_t* out, size_t ostride) {
     for (uint32_t x = 0; x < pw; ++x) out[x] = resid[x];
     for (uint32_t r = 1; r < ph; ++r) {
         const uint8_t* above = out + (size_t)(r - 1) * ostride;
         for (uint32_t x = 0; x < pw; ++x) {
-            int pred = predict_at(above, x, pw);
+            int pred = predictor == L3O_PREDICTOR_ORIGINAL
+                           ? predict_original_at(above, out + (size_t)r * ostride, x)
+                           : predict_at(above, x, pw);
             out[r * ostride + x] = (uint8_t)(pred + resid[r * rstride + x]);
         }
     }
@@ -206,6 +233,15 @@ void l3o_predict_batch(const uint8_t* tl, const uint8_t* t, const uint8_t* tr,
     for (size_t i = 0; i < n; ++i) out[i] = l3o_predict(tl[i], t[i], tr[i]);
 }
 
+uint8_t l3o_predict_original(uint8_t left, uint8_t top, uint8_t top_left) {
+    return (uint8_t)predict_original_int(left, top, top_left);
+}
+
+void l3o_predict_original_batch(const uint8_t* left, const uint8_t* top, const uint8_t* top_left,
+                                uint8_t* out, size_t n) {
+    for (size_t i = 0; i < n; ++i) out[i] = l3o_predict_original(left[i], top[i], top_left[i]);
+}
+
 size_t l3o_encode_bound(uint32_t width, uint32_t height, uint32_t patch) {
     if (patch == 0) patch = l3o_patch_rule(width, height);
     uint64_t px = ceil_div(width, patch), py = ceil_div(height, patch);
@@ -217,8 +253,16 @@ size_t l3o_encode_bound(uint32_t width, uint32_t height, uint32_t patch) {
 int l3o_encode(const uint8_t* rgb, uint32_t width, uint32_t height, size_t row_stride,
                uint32_t patch, int width_mode, uint8_t* out, size_t out_cap,
                size_t* out_len) {
+    return l3o_encode_with(rgb, width, height, row_stride, patch, width_mode,
+                           L3O_PREDICTOR_CUSTOM, out, out_cap, out_len);
+}
+
+int l3o_encode_with(const uint8_t* rgb, uint32_t width, uint32_t height, size_t row_stride,
+                    uint32_t patch, int width_mode, int predictor, uint8_t* out, size_t out_cap,
+                    size_t* out_len) {
     if (!rgb || !out || !out_len || width == 0 || height == 0 || patch > 255 ||
-        row_stride < (size_t)width * 3 || width_mode < 0 || width_mode > 2)
+        row_stride < (size_t)width * 3 || width_mode < 0 || width_mode > 2 ||
+        (predictor != L3O_PREDICTOR_CUSTOM && predictor != L3O_PREDICTOR_ORIGINAL))
         return L3O_ERR_ARG;
     if (patch == 0) patch = l3o_patch_rule(width, height);
     const uint32_t px = ceil_div(width, patch), py = ceil_div(height, patch);
@@ -239,7 +283,7 @@ int l3o_encode(const uint8_t* rgb, uint32_t width, uint32_t height, size_t row_s
                 uint32_t ph = (height - y0 < patch) ? height - y0 : patch;
                 BitWriter bw;
                 encode_patch(rgb + (size_t)y0 * row_stride + (size_t)x0 * 3 + c, row_stride, 3,
-                             pw, ph, width_mode, bw);
+                             pw, ph, width_mode, predictor, bw);
                 uint64_t flat = (uint64_t)c * patches + (uint64_t)ty * px + tx;
                 if (data_pos > 0xFFFFFFFFull) return L3O_ERR_ARG;
                 store_u32le(out + 13 + 4 * flat, (uint32_t)data_pos);
@@ -271,15 +315,27 @@ int l3o_parse_header(const uint8_t* file, size_t len, l3o_info* info) {
 
 int l3o_decode_patch(const uint8_t* stream, size_t len, uint32_t pw, uint32_t ph,
                      uint8_t* out, size_t out_stride) {
-    if (!stream || !out || pw == 0 || ph == 0 || out_stride < pw) return L3O_ERR_ARG;
+    return l3o_decode_patch_with(stream, len, pw, ph, L3O_PREDICTOR_CUSTOM, out, out_stride);
+}
+
+int l3o_decode_patch_with(const uint8_t* stream, size_t len, uint32_t pw, uint32_t ph,
+                          int predictor, uint8_t* out, size_t out_stride) {
+    if (!stream || !out || pw == 0 || ph == 0 || out_stride < pw ||
+        (predictor != L3O_PREDICTOR_CUSTOM && predictor != L3O_PREDICTOR_ORIGINAL))
+        return L3O_ERR_ARG;
     std::vector<uint8_t> resid((size_t)pw * ph);
     int rc = unpack_patch(stream, len, pw, ph, resid.data(), pw);
     if (rc != L3O_OK) return rc;
-    unfilter_patch(resid.data(), pw, pw, ph, out, out_stride);
+    unfilter_patch(resid.data(), pw, pw, ph, predictor, out, out_stride);
     return L3O_OK;
 }
 
 int l3o_decode(const uint8_t* file, size_t len, uint8_t* rgb, size_t row_stride) {
+    return l3o_decode_with(file, len, L3O_PREDICTOR_CUSTOM, rgb, row_stride);
+}
+
+int l3o_decode_with(const uint8_t* file, size_t len, int predictor, uint8_t* rgb,
+                    size_t row_stride) {
     l3o_info info;
     int rc = l3o_parse_header(file, len, &info);
     if (rc != L3O_OK) return rc;
@@ -289,7 +345,7 @@ int l3o_decode(const uint8_t* file, size_t len, uint8_t* rgb, size_t row_stride)
         [&](uint32_t c, uint32_t x0, uint32_t y0, uint32_t pw, uint32_t ph,
             const uint8_t* stream, size_t slen) -> int {
             pixels.assign((size_t)pw * ph, 0);
-            int r = l3o_decode_patch(stream, slen, pw, ph, pixels.data(), pw);
+            int r = l3o_decode_patch_with(stream, slen, pw, ph, predictor, pixels.data(), pw);
             if (r != L3O_OK) return r;
             for (uint32_t y = 0; y < ph; ++y)
                 for (uint32_t x = 0; x < pw; ++x)

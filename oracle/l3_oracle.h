@@ -28,7 +28,9 @@
  * Pins (tests/test_oracle_*.py): the 74/65/9 worked example of Section 4.2,
  * the closed-form size of a uniform-random FHD image (Table "compratio",
  * 1.02x), exhaustive predictor properties, brute force over tiny images,
- * hand-assembled streams, ramps and constant images, segment independence.
+ * hand-assembled streams, ramps and constant images, segment independence;
+ * the original Paeth predictor against an independent PNG decoder (its filter
+ * type 4 is that predictor).
  * Unpinned against the authors' own files (not available): tie order, border
  * rule and the byte-level conventions above -- "parity unpinned" for
  * interoperability; the build is self-consistent only.
@@ -68,6 +70,16 @@ uint8_t l3o_predict(uint8_t top_left, uint8_t top, uint8_t top_right);
 void l3o_predict_batch(const uint8_t* tl, const uint8_t* t, const uint8_t* tr,
                        uint8_t* out, size_t n);
 
+/* Section 4.2, what the custom filter replaces: the original Paeth filter on
+ * left, top and top-left (reference value left + top - top_left, nearest wins,
+ * ties left, top, top-left).  Only the ablation of Section 5.5 uses it: the
+ * same container and base-delta stage, with this predictor in rows >= 1 (the
+ * first row stays raw; in the first column the prediction is "top"). */
+enum { L3O_PREDICTOR_CUSTOM = 0, L3O_PREDICTOR_ORIGINAL = 1 };
+uint8_t l3o_predict_original(uint8_t left, uint8_t top, uint8_t top_left);
+void l3o_predict_original_batch(const uint8_t* left, const uint8_t* top,
+                                const uint8_t* top_left, uint8_t* out, size_t n);
+
 /* Upper bound of the file size for any content. */
 size_t l3o_encode_bound(uint32_t width, uint32_t height, uint32_t patch);
 
@@ -78,10 +90,19 @@ int l3o_encode(const uint8_t* rgb_hwc, uint32_t width, uint32_t height,
                size_t row_stride, uint32_t patch, int width_mode,
                uint8_t* out, size_t out_cap, size_t* out_len);
 
+/* As l3o_encode, with the filter of stage 1 chosen by `predictor`. */
+int l3o_encode_with(const uint8_t* rgb_hwc, uint32_t width, uint32_t height,
+                    size_t row_stride, uint32_t patch, int width_mode, int predictor,
+                    uint8_t* out, size_t out_cap, size_t* out_len);
+
 int l3o_parse_header(const uint8_t* file, size_t len, l3o_info* info);
 
 /* Whole file -> interleaved RGB (HWC), rows row_stride bytes apart. */
 int l3o_decode(const uint8_t* file, size_t len, uint8_t* rgb_hwc, size_t row_stride);
+
+/* As l3o_decode, for a file whose stage 1 used `predictor`. */
+int l3o_decode_with(const uint8_t* file, size_t len, int predictor, uint8_t* rgb_hwc,
+                    size_t row_stride);
 
 /* Whole file -> the residual planes (after base-delta decoding, before the
  * inverse filter), planar: plane c at out + c*width*height, rows width apart. */
@@ -90,6 +111,9 @@ int l3o_decode_residuals(const uint8_t* file, size_t len, uint8_t* planes);
 /* One patch stream of pw x ph pixels -> pixels, rows out_stride apart. */
 int l3o_decode_patch(const uint8_t* stream, size_t len, uint32_t pw, uint32_t ph,
                      uint8_t* out, size_t out_stride);
+
+int l3o_decode_patch_with(const uint8_t* stream, size_t len, uint32_t pw, uint32_t ph,
+                          int predictor, uint8_t* out, size_t out_stride);
 
 /* Training-input epilogue (not in the paper; defined by the benchmark
  * configuration): crop window at (x0,y0) of crop_w x crop_h, optional
