@@ -115,6 +115,58 @@ def measure_load_decode(torch, l3, ctx, images, files, infos, stream):
                     "double-buffered against the decode"}
 
 
+def measure_ablation(torch, l3, ctx, images, files, infos, stream, patch, product_ms):
+    """The four decoder variants of Section 5.5 (plain kernels, one wave per patch and
+    channel), each checked against the input images, plus two of them with the patches
+    of an image taken one after another."""
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+        files_orig = list(pool.map(lambda im: l3.encode_cpu(im, patch, original_filter=True), images))
+    sets = {}
+    for custom, fl in ((False, files_orig), (True, files)):
+        dfiles = [torch.from_numpy(np.frombuffer(f, dtype=np.uint8).copy()).cuda() for f in fl]
+        finfos = [l3.peek_header(f) for f in fl]
+        outs = [torch.empty((im.shape[0], im.shape[1] * 3), dtype=torch.uint8, device="cuda")
+                for im in images]
+        sets[custom] = (l3.PreparedBatch(dfiles, finfos, outs), outs, sum(map(len, fl)))
+    PB, CF, SP = l3.ABLATION_PIXEL_BD, l3.ABLATION_CUSTOM_FILTER, l3.ABLATION_SERIAL_PATCHES
+    variants = [("baseline: original filter, one lane per patch for both stages", 0),
+                ("+pixel-wise base-delta", PB),
+                ("+custom filter", CF),
+                ("+pixel-wise base-delta +custom filter", PB | CF),
+                ("baseline, patches of an image in turn", SP),
+                ("+both, patches of an image in turn", PB | CF | SP)]
+    rows = []
+    for name, v in variants:
+        batch, outs, _ = sets[bool(v & CF)]
+        for t in outs:
+            t.zero_()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        l3.ablation_decode_batch(ctx, batch, v, stream=stream)       # uploads the table, warms up
+        torch.cuda.synchronize()
+        for k in (0, len(images) - 1):
+            if not np.array_equal(outs[k].cpu().numpy().reshape(images[k].shape), images[k]):
+                raise SystemExit("bench.py: ablation variant %d decoded wrong pixels" % v)
+        e0.record(stream)
+        l3.ablation_decode_batch(ctx, batch, v, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        first = e0.elapsed_time(e1)
+        reps = int(max(1, min(50, 300.0 / max(first, 1e-3))))
+        e0.record(stream)
+        for _ in range(reps):
+            l3.ablation_decode_batch(ctx, batch, v, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        rows.append({"variant": name, "flags": v, "ms_per_batch": e0.elapsed_time(e1) / reps, "reps": reps})
+    base = rows[0]["ms_per_batch"]
+    for r in rows:
+        r["normalized"] = r["ms_per_batch"] / base
+    return {"variants": rows, "tuned_decoder_ms": product_ms,
+            "file_bytes": {"original_filter": sets[False][2], "custom_filter": sets[True][2]},
+            "note": "plain kernels of l3_ablation_decode_batch; normalised to the baseline as in the "
+                    "paper's figure; the tuned decoder is l3_decode_batch on the same batch"}
+
+
 def measure_encode(torch, l3, ctx, images, files, stream, patch):
     """l3_encode_batch on the workload's images; the files must equal l3_encode_cpu's."""
     n = len(images)
@@ -210,6 +262,10 @@ def main():
                     help="also time Load+Decode: the files start in pinned host memory, are copied "
                          "to the GPU on a second stream and decoded, double-buffered (the paper's "
                          "data-preparation measurement, Section 5.3, with host RAM as the source)")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the decoder variants of the paper's ablation (Section 5.5): "
+                         "original or custom filter, one lane or one lane per pixel for base-delta, "
+                         "with and without patch-level parallelism")
     ap.add_argument("--encode", action="store_true",
                     help="also time l3_encode_batch on the same images (pixels resident in HBM) "
                          "and check its files against l3_encode_cpu's")
@@ -355,6 +411,9 @@ def main():
         result["overlap"] = measure_overlap(torch, step, stream, args.steps, ms_per_step)
     if args.load_pipeline and not fused:
         result["load_decode"] = measure_load_decode(torch, l3, ctx, images, files, infos, stream)
+    if args.ablation and not fused:
+        result["ablation"] = measure_ablation(torch, l3, ctx, images, files, infos, stream,
+                                              args.patch, result["roofline"]["launch_ms"])
     if args.encode:
         result["encode"] = measure_encode(torch, l3, ctx, images, files, stream, args.patch)
 

@@ -12,7 +12,7 @@ from . import build as _build
 __all__ = [
     "OracleError", "patch_rule", "predict", "predict_batch", "encode", "parse_header",
     "decode", "decode_residuals", "decode_patch", "crop_normalize", "f32_to_bf16",
-    "f32_to_f16", "ERR_ARG", "ERR_MAGIC", "ERR_TRUNCATED", "ERR_CORRUPT", "ERR_SPACE",
+    "f32_to_f16", "predict_original_batch", "PREDICTOR_CUSTOM", "PREDICTOR_ORIGINAL", "ERR_ARG", "ERR_MAGIC", "ERR_TRUNCATED", "ERR_CORRUPT", "ERR_SPACE",
 ]
 
 OK, ERR_ARG, ERR_MAGIC, ERR_TRUNCATED, ERR_CORRUPT, ERR_SPACE = range(6)

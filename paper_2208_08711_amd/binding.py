@@ -19,7 +19,7 @@ BF16, FP16 = 0, 1
 EXPORTED_SYMBOLS = (
     "l3_status_string", "l3_default_patch", "l3_encode_bound", "l3_encode_cpu", "l3_peek_header",
     "l3_ctx_create", "l3_ctx_destroy", "l3_decode_batch", "l3_decode_crop_normalize_batch",
-    "l3_encode_batch",
+    "l3_encode_batch", "l3_ablation_encode_cpu", "l3_ablation_decode_batch",
 )
 
 
@@ -77,6 +77,13 @@ def _load():
     lib.l3_encode_cpu.argtypes = [u8p, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_size_t,
                                   ctypes.c_uint8, u8p, ctypes.c_size_t,
                                   ctypes.POINTER(ctypes.c_size_t)]
+    lib.l3_ablation_encode_cpu.restype = ctypes.c_int
+    lib.l3_ablation_encode_cpu.argtypes = [u8p, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_size_t,
+                                           ctypes.c_uint8, ctypes.c_int, u8p, ctypes.c_size_t,
+                                           ctypes.POINTER(ctypes.c_size_t)]
+    lib.l3_ablation_decode_batch.restype = ctypes.c_int
+    lib.l3_ablation_decode_batch.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Item), ctypes.c_int,
+                                             ctypes.c_int, ctypes.c_void_p]
     lib.l3_peek_header.restype = ctypes.c_int
     lib.l3_peek_header.argtypes = [u8p, ctypes.c_size_t, ctypes.POINTER(Info)]
     lib.l3_ctx_create.restype = ctypes.c_int
@@ -120,8 +127,9 @@ def encode_bound(width, height, patch=0):
     return int(_load().l3_encode_bound(width, height, patch))
 
 
-def encode_cpu(rgb, patch=0):
-    """rgb: uint8 numpy array [H, W, 3] (host).  Returns the L3 file as bytes."""
+def encode_cpu(rgb, patch=0, original_filter=False):
+    """rgb: uint8 numpy array [H, W, 3] (host).  Returns the L3 file as bytes.
+    original_filter=True writes the ablation baseline's files (l3_ablation_encode_cpu)."""
     rgb = np.asarray(rgb)
     if rgb.dtype != np.uint8 or rgb.ndim != 3 or rgb.shape[2] != 3:
         raise ValueError("expected uint8 [H, W, 3]")
@@ -132,8 +140,12 @@ def encode_cpu(rgb, patch=0):
     cap = lib.l3_encode_bound(w, h, patch)
     out = np.empty(max(cap, 1), dtype=np.uint8)
     n = ctypes.c_size_t(0)
-    _check(lib.l3_encode_cpu(_u8(rgb), w, h, rgb.strides[0], patch, _u8(out), cap, ctypes.byref(n)),
-           "l3_encode_cpu")
+    if original_filter:
+        _check(lib.l3_ablation_encode_cpu(_u8(rgb), w, h, rgb.strides[0], patch, 1, _u8(out), cap,
+                                          ctypes.byref(n)), "l3_ablation_encode_cpu")
+    else:
+        _check(lib.l3_encode_cpu(_u8(rgb), w, h, rgb.strides[0], patch, _u8(out), cap,
+                                 ctypes.byref(n)), "l3_encode_cpu")
     return out[:n.value].tobytes()
 
 
@@ -203,6 +215,15 @@ def decode_batch(ctx, files, infos, outs, layout=LAYOUT_HWC, status=None, stream
     _check(_load().l3_decode_batch(ctx.handle, arr, n, layout,
                                    ctypes.c_void_p(status.data_ptr() if status is not None else None),
                                    _stream_ptr(stream)), "l3_decode_batch")
+
+
+ABLATION_PIXEL_BD, ABLATION_CUSTOM_FILTER, ABLATION_SERIAL_PATCHES = 1, 2, 4
+
+
+def ablation_decode_batch(ctx, batch, variant, stream=None):
+    """l3_ablation_decode_batch on a PreparedBatch (interleaved RGB outputs)."""
+    _check(_load().l3_ablation_decode_batch(ctx.handle, batch.items, batch.n, int(variant),
+                                            _stream_ptr(stream)), "l3_ablation_decode_batch")
 
 
 class PreparedBatch:

@@ -13,7 +13,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libl3.so")
 SOURCES = [os.path.join(CSRC, "l3_host.cpp"), os.path.join(CSRC, "l3_device.hip"),
-           os.path.join(CSRC, "l3_encode.hip")]
+           os.path.join(CSRC, "l3_encode.hip"), os.path.join(CSRC, "l3_ablation.hip")]
 
 
 def build(verbose: bool = False) -> str:

@@ -14,6 +14,9 @@ constexpr int kSlots = 4;   /* descriptor staging slots: calls in flight before 
 struct L3EncodeState;                          /* workspace of l3_encode_batch, owned by its file */
 void l3_encode_state_free(L3EncodeState* s);   /* NULL allowed */
 
+struct L3AblationState;                        /* workspace of l3_ablation_decode_batch */
+void l3_ablation_state_free(L3AblationState* s);   /* NULL allowed */
+
 struct l3_ctx {
     int device = 0;
     L3ImageDesc* scratch = nullptr;       /* host: descriptors of the call being planned */
@@ -26,6 +29,7 @@ struct l3_ctx {
     bool pending[kSlots] = {};
     int next = 0;
     L3EncodeState* enc = nullptr;
+    L3AblationState* abl = nullptr;
 };
 
 /* Makes the context's device current for the lifetime of the guard. */

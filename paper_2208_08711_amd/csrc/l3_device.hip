@@ -919,6 +919,7 @@ void l3_ctx_destroy(l3_ctx* ctx) {
     release_slots(ctx);
     std::free(ctx->scratch);
     l3_encode_state_free(ctx->enc);
+    l3_ablation_state_free(ctx->abl);
     delete ctx;
 }
 

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "l3_internal.h"
+#include "l3_ablation.h"
 
 namespace {
 
@@ -64,9 +65,22 @@ inline unsigned bits_for(unsigned range) {
     return n;
 }
 
-/* Encodes one pw x ph patch held as a dense plane. */
-void encode_plane_patch(const uint8_t* plane, uint32_t pw, uint32_t ph, std::vector<uint8_t>& dst,
-                        std::vector<int>& row) {
+/* Section 4.2, the filter the custom one replaces: nearest of left, top, top-left to
+ * left + top - top_left, ties in that order.  Distances are |T-C| (for L), |L-C| (for T)
+ * and |L+T-2C| (for C = top-left). */
+inline int nearest_original(int left, int top, int corner) {
+    int d_l = top > corner ? top - corner : corner - top;
+    int d_t = left > corner ? left - corner : corner - left;
+    int s = left + top - 2 * corner;
+    int d_c = s < 0 ? -s : s;
+    if (d_l <= d_t && d_l <= d_c) return left;
+    return d_t <= d_c ? top : corner;
+}
+
+/* Encodes one pw x ph patch held as a dense plane.  original_filter selects the
+ * left/top/top-left predictor (ablation baseline of Section 5.5) for rows >= 1. */
+void encode_plane_patch(const uint8_t* plane, uint32_t pw, uint32_t ph, bool original_filter,
+                        std::vector<uint8_t>& dst, std::vector<int>& row) {
     BitSink sink(dst);
     row.resize(pw);
     for (uint32_t y = 0; y < ph; ++y) {
@@ -75,6 +89,10 @@ void encode_plane_patch(const uint8_t* plane, uint32_t pw, uint32_t ph, std::vec
         int vmin, vmax;
         if (y == 0) {
             for (uint32_t x = 0; x < pw; ++x) row[x] = cur[x];
+        } else if (original_filter) {
+            row[0] = (int8_t)(uint8_t)(cur[0] - up[0]);
+            for (uint32_t x = 1; x < pw; ++x)
+                row[x] = (int8_t)(uint8_t)(cur[x] - nearest_original(cur[x - 1], up[x], up[x - 1]));
         } else {
             row[0] = (int8_t)(uint8_t)(cur[0] - up[0]);
             for (uint32_t x = 1; x + 1 < pw; ++x)
@@ -128,8 +146,12 @@ size_t l3_encode_bound(uint32_t width, uint32_t height, uint8_t patch) {
     return (size_t)(kFixedHeader + 12ull * tx * ty + 3ull * per_channel);
 }
 
-l3_status l3_encode_cpu(const uint8_t* rgb, uint32_t width, uint32_t height, size_t row_stride,
-                        uint8_t patch, uint8_t* out, size_t out_cap, size_t* out_len) {
+}  // extern "C"
+
+namespace {
+l3_status encode_file(const uint8_t* rgb, uint32_t width, uint32_t height, size_t row_stride,
+                      uint8_t patch, bool original_filter, uint8_t* out, size_t out_cap,
+                      size_t* out_len) {
     if (!rgb || !out || !out_len || width == 0 || height == 0 ||
         row_stride < (size_t)width * 3)
         return L3_ERR_INVALID_ARG;
@@ -158,7 +180,7 @@ l3_status l3_encode_cpu(const uint8_t* rgb, uint32_t width, uint32_t height, siz
                     for (uint32_t x = 0; x < pw; ++x) plane[(size_t)y * pw + x] = src[3 * (size_t)x];
                 }
                 coded.clear();
-                encode_plane_patch(plane.data(), pw, ph, coded, row);
+                encode_plane_patch(plane.data(), pw, ph, original_filter, coded, row);
                 if (pos > 0xFFFFFFFFull) return L3_ERR_UNSUPPORTED;
                 if (header + pos + coded.size() > out_cap) return L3_ERR_BUFFER_TOO_SMALL;
                 wr32(out + kFixedHeader + 4 * ((uint64_t)c * p + (uint64_t)j * tx + i), (uint32_t)pos);
@@ -167,6 +189,21 @@ l3_status l3_encode_cpu(const uint8_t* rgb, uint32_t width, uint32_t height, siz
             }
     *out_len = (size_t)(header + pos);
     return L3_OK;
+}
+}  // namespace
+
+extern "C" {
+
+l3_status l3_encode_cpu(const uint8_t* rgb, uint32_t width, uint32_t height, size_t row_stride,
+                        uint8_t patch, uint8_t* out, size_t out_cap, size_t* out_len) {
+    return encode_file(rgb, width, height, row_stride, patch, false, out, out_cap, out_len);
+}
+
+l3_status l3_ablation_encode_cpu(const uint8_t* rgb, uint32_t width, uint32_t height,
+                                 size_t row_stride, uint8_t patch, int original_filter,
+                                 uint8_t* out, size_t out_cap, size_t* out_len) {
+    return encode_file(rgb, width, height, row_stride, patch, original_filter != 0, out, out_cap,
+                       out_len);
 }
 
 l3_status l3_peek_header(const uint8_t* file, size_t len, l3_info* info) {

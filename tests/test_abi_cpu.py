@@ -17,7 +17,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "l3.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", name)).read()
+                   for name in sorted(os.listdir(os.path.join(ROOT, "include"))) if name.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(l3_[a-z0-9_]+)\s*\(", text)))
 
@@ -60,6 +61,19 @@ def test_product_encoder_matches_oracle_bytes():
             n = patch or oracle.patch_rule(im.shape[1], im.shape[0])
             assert (info.width, info.height, info.patch) == (im.shape[1], im.shape[0], n)
             assert info.header_bytes == 13 + 12 * info.patches_per_channel
+
+
+def test_product_encoder_original_filter_matches_oracle_bytes():
+    """The ablation baseline's encoder (original Paeth filter, Section 5.5) against the oracle."""
+    images = synth.config1() + [synth.voronoi_scene(3, 300, 200), synth.uniform_bytes(4, 129, 70),
+                                synth.gradient_noise(5, 1, 9, 2.0), synth.gradient_noise(6, 9, 1, 2.0)]
+    for im in images:
+        for patch in (0, 7, 32, 128):
+            if patch == 7 and im.size > 30000:
+                continue
+            a = l3.encode_cpu(im, patch, original_filter=True)
+            assert a == oracle.encode(im, patch, predictor=oracle.PREDICTOR_ORIGINAL), (im.shape, patch)
+            assert len(a) <= l3.encode_bound(im.shape[1], im.shape[0], patch)
 
 
 def test_encode_cpu_errors():

@@ -1,0 +1,93 @@
+"""GPU parity of the ablation decoders (arxiv 2208.08711 Section 5.5): every variant,
+called through the C ABI, must give the oracle's pixels byte for byte."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2208_08711_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def l3():
+    import paper_2208_08711_amd as mod
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return mod
+
+
+@pytest.fixture(scope="module")
+def ctx(l3):
+    c = l3.Context(0)
+    yield c
+    c.close()
+
+
+def _images():
+    return [synth.gradient_noise(21, 150, 70, 2.0), synth.voronoi_scene(22, 131, 129, sites=9),
+            synth.uniform_bytes(23, 65, 33), synth.cosine_field(24, 64, 64),
+            np.zeros((5, 200, 3), np.uint8), synth.gradient_noise(25, 1, 40, 2.0),
+            synth.gradient_noise(26, 300, 1, 2.0)]
+
+
+def _run(l3, ctx, files, variant, pad=5, poison=0xA7):
+    infos = [l3.peek_header(f) for f in files]
+    dfiles = [torch.from_numpy(np.frombuffer(f, dtype=np.uint8).copy()).cuda() for f in files]
+    outs = [torch.full((inf.height, 3 * inf.width + pad), poison, dtype=torch.uint8, device="cuda")
+            for inf in infos]
+    batch = l3.PreparedBatch(dfiles, infos, outs, row_strides=[3 * inf.width + pad for inf in infos])
+    l3.ablation_decode_batch(ctx, batch, variant)
+    torch.cuda.synchronize()
+    res = []
+    for t, inf in zip(outs, infos):
+        a = t.cpu().numpy()
+        assert (a[:, 3 * inf.width:] == poison).all(), "wrote outside the image rows"
+        res.append(a[:, :3 * inf.width].reshape(inf.height, inf.width, 3))
+    return res
+
+
+@pytest.mark.parametrize("variant", range(8))
+@pytest.mark.parametrize("patch", [7, 32, 64, 128])
+def test_ablation_variant_matches_oracle(l3, ctx, variant, patch):
+    custom = bool(variant & l3.ABLATION_CUSTOM_FILTER)
+    predictor = oracle.PREDICTOR_CUSTOM if custom else oracle.PREDICTOR_ORIGINAL
+    images = _images()
+    files = [l3.encode_cpu(im, patch, original_filter=not custom) for im in images]
+    want = [oracle.decode(f, predictor=predictor) for f in files]
+    print(f"ablation variant={variant} patch={patch} images={len(images)}", flush=True)
+    got = _run(l3, ctx, files, variant)
+    for k, (g, w_, im) in enumerate(zip(got, want, images)):
+        assert np.array_equal(w_, im)
+        assert np.array_equal(g, w_), (k, im.shape)
+
+
+def test_ablation_non_canonical_widths(l3, ctx):
+    """Streams with wider-than-needed rows (valid, non-canonical) decode the same."""
+    im = synth.voronoi_scene(27, 140, 90, sites=9)
+    for predictor, variant in ((oracle.PREDICTOR_ORIGINAL, 0), (oracle.PREDICTOR_ORIGINAL, 1),
+                               (oracle.PREDICTOR_CUSTOM, 2), (oracle.PREDICTOR_CUSTOM, 3)):
+        for mode in (1, 2):
+            f = oracle.encode(im, 64, width_mode=mode, predictor=predictor)
+            print(f"ablation non-canonical variant={variant} mode={mode}", flush=True)
+            assert np.array_equal(_run(l3, ctx, [f], variant)[0], im)
+
+
+def test_ablation_rejects_bad_arguments(l3, ctx):
+    im = synth.gradient_noise(28, 40, 30, 2.0)
+    f = l3.encode_cpu(im, 32)
+    info = l3.peek_header(f)
+    d = torch.from_numpy(np.frombuffer(f, dtype=np.uint8).copy()).cuda()
+    out = torch.zeros((30, 120), dtype=torch.uint8, device="cuda")
+    with pytest.raises(l3.L3Error) as e:
+        l3.ablation_decode_batch(ctx, l3.PreparedBatch([d], [info], [out]), 8)
+    assert e.value.code == 1
+    with pytest.raises(l3.L3Error) as e:
+        l3.ablation_decode_batch(ctx, l3.PreparedBatch([d], [info], [out], row_strides=[100]), 3)
+    assert e.value.code == 1
+    f255 = l3.encode_cpu(im, 255)
+    d255 = torch.from_numpy(np.frombuffer(f255, dtype=np.uint8).copy()).cuda()
+    with pytest.raises(l3.L3Error) as e:
+        l3.ablation_decode_batch(ctx, l3.PreparedBatch([d255], [l3.peek_header(f255)], [out]), 3)
+    assert e.value.code == 6
