@@ -249,7 +249,8 @@ def measure_encode(torch, l3, ctx, images, files, stream, patch):
     out = sum(got)
     return {"ms_per_batch": ms, "images_per_s": n / (ms * 1e-3), "raw_GBps": raw / (ms * 1e-3) / 1e9,
             "hbm_fraction": (raw + out) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "note": "three kernels per call (measure, layout, pack); the pixels are read twice"}
+            "note": "three kernels per call: strip (filter, row min/max, bit packing into per-patch "
+                    "slots), layout (prefix sum of the patch sizes), compact (slots to the file)"}
 
 
 def measure_overlap(torch, step, stream, steps, decode_alone_ms):

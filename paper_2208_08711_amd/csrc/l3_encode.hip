@@ -9,16 +9,21 @@
  * base, minimal width, deltas packed).  Section 4.3: patches concatenated, their
  * offsets recorded in three arrays behind a 13-byte header.
  *
- * Three kernels per call:
- *   measure  one wave per (patch, channel): row widths -> patch byte size;
+ * Patch sizes 32, 64 and 128 (the ones the paper's rule picks) take three kernels:
+ *   strip    a workgroup of three waves (one per channel) owns a strip of adjacent
+ *            patches, 4 pixels per lane as two packed pairs of 16-bit fields: per
+ *            row it filters, reduces min and max over the patch's lanes, packs the
+ *            deltas with LDS atomic OR into a small ring per patch and streams the
+ *            finished 16-byte granules to a fixed-size slot of a workspace; the
+ *            patch's byte size goes to a table;
  *   layout   one workgroup per image: exclusive prefix sum of the patch sizes ->
  *            header, offset arrays, file length (this is where a scan belongs: the
  *            addends are all known);
- *   pack     one wave per (patch, channel): rows again, bits assembled in LDS with
- *            atomic OR (a row's position is the running sum of the rows before
- *            it), then copied to the file.
- * The forward filter needs no row recurrence, so a wave just walks the rows with
- * the row above in registers and lane shifts for the neighbours.
+ *   compact  copies every slot to its place in the file.
+ * Any other patch size up to 128 takes the plain route: measure (one wave per patch
+ * and channel walks the rows for the sizes), layout, pack (walks them again and
+ * writes the bits).  The forward filter needs no row recurrence: the row above is
+ * the original one, kept in registers, with lane shifts for the neighbours.
  */
 #include <hip/hip_runtime.h>
 
@@ -27,6 +32,7 @@
 #include <new>
 
 #include "l3_ctx.h"
+#include "l3_gfx950.h"
 
 namespace {
 
@@ -42,7 +48,8 @@ struct L3EncodeDesc {
     uint32_t patch;
     uint32_t sizes_base;     /* first entry of this image in the sizes scratch */
     uint32_t status_index;
-    uint32_t pad_;
+    uint32_t strips_x;       /* strip route: wave strips per patch row */
+    uint64_t slots_base;     /* strip route: byte offset of this image's first slot in the workspace */
 };
 
 typedef __attribute__((address_space(1))) uint32_t global_u32_unaligned __attribute__((aligned(1)));
@@ -144,12 +151,277 @@ __device__ uint32_t walk_patch(const L3EncodeDesc& d, uint32_t c, uint32_t tx, u
     return pos;
 }
 
+
+/* ---- the strip route: N in {32, 64, 128} ------------------------------------ */
+
+template <int N>
+struct StripGeom {
+    static constexpr int LPT = N / 4;              /* lanes per patch, 4 pixels each */
+    static constexpr int TPW = 64 / LPT;           /* patches per wave */
+    static constexpr int P = 3;                    /* rows between two flushes of the rings */
+    static constexpr int ROW_MAX = N + 3;          /* bytes a row can touch: ceil((12 + 8N)/8) + 1 */
+    static constexpr int RING = 8 * N;             /* ring bytes per patch and channel */
+    /* the longest patch stream, rounded up to whole 16-byte granules */
+    static constexpr uint32_t SLOT = ((uint32_t)N * (12 + 8 * N) / 8 + 1 + 15) / 16 * 16;
+    /* one flush round (a granule per lane of the patch) takes everything that P rows
+     * and a pending partial granule can have completed, and the ring holds it */
+    static_assert(LPT * 16 >= P * ROW_MAX + 15, "a flush round empties a period");
+    static_assert(RING >= 2 * (P * ROW_MAX + 16), "ring holds a period beside the granules being cleared");
+    static_assert((RING & (RING - 1)) == 0, "ring size is a power of two");
+};
+
+__host__ __device__ constexpr uint32_t strip_slot_bytes(uint32_t n) {
+    return n == 32 ? StripGeom<32>::SLOT : n == 64 ? StripGeom<64>::SLOT : StripGeom<128>::SLOT;
+}
+
+typedef __attribute__((address_space(1))) const u32x3_any global_const_u32x3_any;
+typedef __attribute__((address_space(1))) u32x4 global_u32x4;
+
+__device__ __forceinline__ uint32_t pk_sub_u16_sat(uint32_t a, uint32_t b) {   /* max(a - b, 0) per field */
+    uint32_t d;
+    asm("v_pk_sub_u16 %0, %1, %2 clamp" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2, a),
+                                                                  __builtin_bit_cast(u16x2, b)));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+}
+
+/* Minimum of both 16-bit fields, separately, over the LPT lanes of a patch; every
+ * lane gets the result.  Butterfly: lane ^ 1, ^ 2 inside quads, then mirrors inside 8
+ * and 16 lanes, then the swap of neighbouring 16-lane rows. */
+template <int LPT>
+__device__ __forceinline__ uint32_t patch_min_u16x2(uint32_t v) {
+    v = pk_min_u16(v, dpp_move<0xB1>(v));    /* quad_perm [1,0,3,2] */
+    v = pk_min_u16(v, dpp_move<0x4E>(v));    /* quad_perm [2,3,0,1] */
+    v = pk_min_u16(v, dpp_move<0x141>(v));   /* row_half_mirror */
+    if (LPT >= 16) v = pk_min_u16(v, dpp_move<0x140>(v));   /* row_mirror */
+    if (LPT >= 32) {
+        const auto both = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        v = pk_min_u16((uint32_t)both[0], (uint32_t)both[1]);
+    }
+    return v;
+}
+
+/* One strip: TPW adjacent patches of one patch row, channel C. */
+template <int N, int C>
+__device__ __forceinline__ void encode_strip(const L3EncodeDesc& d, uint32_t* __restrict__ sizes,
+                                             uint8_t* __restrict__ slots, uint32_t* ring_words) {
+    using G = StripGeom<N>;
+    constexpr int LPT = G::LPT, TPW = G::TPW, P = G::P, RING = G::RING;
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t g = lane / LPT, xl = lane % LPT;
+    const uint32_t ty = blockIdx.x / d.strips_x, strip = blockIdx.x - ty * d.strips_x;
+    const uint32_t tx = strip * TPW + g;
+    const bool active = tx < d.tiles_x;
+    const uint32_t x0 = tx * N, y0 = ty * N;
+    const uint32_t pw = active ? min((uint32_t)N, d.width - x0) : 0u;
+    const uint32_t ph = min((uint32_t)N, d.height - y0);
+    const uint32_t patches = d.tiles_x * d.tiles_y;
+    const uint32_t k = C * patches + ty * d.tiles_x + tx;               /* index in the offset arrays */
+    uint8_t* const slot = slots + d.slots_base + (uint64_t)k * G::SLOT;
+
+    /* this lane's 4 pixels: columns 4 xl .. 4 xl + 3 of the patch, nvalid of them exist */
+    const uint32_t xpix = 4 * xl;
+    const uint32_t nvalid = pw > xpix ? min(4u, pw - xpix) : 0u;
+    const uint8_t* src = d.rgb + (size_t)y0 * d.row_stride + ((size_t)x0 + xpix) * 3;
+
+    /* registers of two 16-bit fields: E = pixels (0, 2), O = pixels (1, 3) */
+    const uint32_t validE = (nvalid > 0 ? 0x0000FFFFu : 0u) | (nvalid > 2 ? 0xFFFF0000u : 0u);
+    const uint32_t validO = (nvalid > 1 ? 0x0000FFFFu : 0u) | (nvalid > 3 ? 0xFFFF0000u : 0u);
+    uint32_t border[2];
+    border[0] = ((xpix == 0 || xpix + 1 == pw) ? 0x0000FFFFu : 0u) | ((xpix + 3 == pw) ? 0xFFFF0000u : 0u);
+    border[1] = ((xpix + 2 == pw) ? 0x0000FFFFu : 0u) | ((xpix + 4 == pw) ? 0xFFFF0000u : 0u);
+    const uint32_t keepE = validE & 0x00FF00FFu, keepO = validO & 0x00FF00FFu;
+
+    /* The residual byte r is looked at as t = r ^ K, K = 0 in the first row (raw,
+     * unsigned) and 0x80 after it (signed byte + 128), so that the unsigned minimum of t
+     * is the row minimum of Section 4.2; u = t ^ 0xFF turns the maximum into a minimum
+     * too.  Fields of pixels that do not exist read 0xFFFF in both. */
+    uint32_t kminE = ~validE, kminO = ~validO;                          /* K = 0 */
+    uint32_t kmaxE = ~validE | keepE, kmaxO = ~validO | keepO;          /* K ^ 0xFF = 0xFF */
+    uint32_t krow = 0;
+
+    auto load_row = [&](uint32_t r) -> u32x3 {
+        u32x3 v = {0, 0, 0};
+        const uint8_t* p = src + (size_t)r * d.row_stride;
+        if (nvalid == 4) {
+            v = *reinterpret_cast<global_const_u32x3_any*>((uintptr_t)p);
+        } else if (nvalid) {
+            uint32_t b[12];
+#pragma unroll
+            for (int i = 0; i < 12; ++i) b[i] = (uint32_t)(i < 9 && (uint32_t)i < 3 * nvalid ? p[i] : 0);
+            v.x = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
+            v.y = b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24);
+            v.z = b[8];
+        }
+        return v;
+    };
+
+    uint32_t* const ring = ring_words + g * (RING / 4);
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)ring;
+    typedef __attribute__((address_space(3))) uint32_t lds_u32;
+    constexpr uint32_t WM = RING / 4 - 1;
+    {
+        u32x4 zero = {0, 0, 0, 0};
+        for (uint32_t i = xl; i < RING / 16; i += LPT) reinterpret_cast<u32x4*>(ring)[i] = zero;
+    }
+    wave_lds_fence();
+
+    /* ORs `nbits`-wide `value` (at most 32 bits) into the ring at bit `pos` */
+    auto put = [&](uint32_t value, uint32_t pos) {
+        const uint32_t w0 = (pos >> 5) & WM, w1 = (w0 + 1) & WM;
+        const uint32_t lo = value << (pos & 31u);
+        const uint32_t hi = (value >> 1) >> (~pos & 31u);
+        __hip_atomic_fetch_or(reinterpret_cast<lds_u32*>(ring_lds + 4 * w0), lo, __ATOMIC_RELAXED,
+                              __HIP_MEMORY_SCOPE_WAVEFRONT);
+        __hip_atomic_fetch_or(reinterpret_cast<lds_u32*>(ring_lds + 4 * w1), hi, __ATOMIC_RELAXED,
+                              __HIP_MEMORY_SCOPE_WAVEFRONT);
+    };
+
+    uint32_t rowpos = 0;       /* bit position of the next row record in the patch stream */
+    uint32_t flushed = 0;      /* granules already in the slot */
+    /* writes granules [flushed, upto) of the stream to the slot and clears them in the ring */
+    auto flush = [&](uint32_t upto) {
+        wave_lds_fence();
+        const uint32_t gi = flushed + xl;
+        if (active && gi < upto) {
+            u32x4* cell = reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + ((gi * 16) & (RING - 1)));
+            const u32x4 v = *cell;
+            const u32x4 zero = {0, 0, 0, 0};
+            *cell = zero;
+            *reinterpret_cast<global_u32x4*>((uintptr_t)(slot + (size_t)gi * 16)) = v;
+        }
+        flushed = max(flushed, upto);
+        wave_lds_fence();
+    };
+
+    uint32_t up[2] = {0, 0};   /* the original row above; zeros above the first row predict 0 */
+    u32x3 next = load_row(0);
+    for (uint32_t r = 0; r < ph; ++r) {
+        const u32x3 raw = next;
+        if (r + 1 < ph) next = load_row(r + 1);
+
+        /* channel C of pixel i is byte 3 i + C of the lane's 12 bytes */
+        uint32_t cur[2];
+        if (C == 0) {
+            cur[0] = __builtin_amdgcn_perm(raw.y, raw.x, 0x0C060C00u);   /* bytes 0, 6 */
+            cur[1] = __builtin_amdgcn_perm(raw.z, raw.x, 0x0C050C03u);   /* bytes 3, 9 */
+        } else if (C == 1) {
+            cur[0] = __builtin_amdgcn_perm(raw.y, raw.x, 0x0C070C01u);   /* bytes 1, 7 */
+            cur[1] = __builtin_amdgcn_perm(raw.z, raw.y, 0x0C060C00u);   /* bytes 4, 10 */
+        } else {
+            cur[0] = __builtin_amdgcn_perm(raw.z, raw.x, 0x0C040C02u);   /* bytes 2, 8 */
+            cur[1] = __builtin_amdgcn_perm(raw.z, raw.y, 0x0C070C01u);   /* bytes 5, 11 */
+        }
+
+        /* Section 4.2 stage 1 on the original row above */
+        const uint32_t from_left = dpp_from_lower_lane(up[1]);
+        const uint32_t from_right = dpp_from_upper_lane(up[0]);
+        uint32_t TL[2], TR[2], pred[2];
+        TL[0] = __builtin_amdgcn_alignbit(up[1], from_left, 16);
+        TR[0] = up[1];
+        TL[1] = up[0];
+        TR[1] = __builtin_amdgcn_alignbit(from_right, up[0], 16);
+        predict_pairs<2>(TL, TR, up, border, pred);
+        const uint32_t rE = __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, cur[0]) -
+                                                                 __builtin_bit_cast(u16x2, pred[0])));
+        const uint32_t rO = __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, cur[1]) -
+                                                                 __builtin_bit_cast(u16x2, pred[1])));
+        /* (r & keep) ^ k */
+        const uint32_t tE = __builtin_amdgcn_bitop3_b32(rE, keepE, kminE, 0x6A);
+        const uint32_t tO = __builtin_amdgcn_bitop3_b32(rO, keepO, kminO, 0x6A);
+        const uint32_t uE = __builtin_amdgcn_bitop3_b32(rE, keepE, kmaxE, 0x6A);
+        const uint32_t uO = __builtin_amdgcn_bitop3_b32(rO, keepO, kmaxO, 0x6A);
+
+        /* stage 2, steps 1-2: row minimum and maximum over the patch */
+        const uint32_t a = pk_min_u16(tE, tO), b = pk_min_u16(uE, uO);
+        uint32_t mm = pk_min_u16(__builtin_amdgcn_perm(b, a, 0x05040100u),    /* (a.lo, b.lo) */
+                                 __builtin_amdgcn_perm(b, a, 0x07060302u));   /* (a.hi, b.hi) */
+        mm = patch_min_u16x2<LPT>(mm);
+        const uint32_t tmin = mm & 0xFFFFu, umin = mm >> 16;     /* min t, 255 - max t */
+        const uint32_t range = (255u - (tmin + umin)) & 0xFFu;   /* masked: lanes without a patch hold no minimum */
+        const uint32_t w = 31u - (uint32_t)__builtin_clz(2u * range + 1u);
+        const uint32_t rec = w | (((tmin ^ krow) & 0xFFu) << 4);
+
+        /* steps 3-4: deltas t - tmin = (255 - tmin) - u, 0 where no pixel exists; the
+         * lane's four deltas as one field of 4 w bits */
+        const uint32_t top1 = (tmin ^ 0xFFu) & 0xFFu, top = top1 | (top1 << 16);
+        const uint32_t dE = pk_sub_u16_sat(top, uE), dO = pk_sub_u16_sat(top, uO);
+        const uint32_t pair = dE | (dO << w);                   /* (d0 | d1 << w, d2 | d3 << w) */
+        const uint32_t group = (pair & 0xFFFFu) | ((pair >> 16) << (2 * w));
+        if (active) {
+            put(group, rowpos + 12 + xpix * w);
+            if (xl == 0) put(rec, rowpos);
+        }
+        rowpos += 12 + pw * w;
+
+        up[0] = cur[0];
+        up[1] = cur[1];
+        if (r == 0) {
+            krow = 0x80u;
+            kminE = ~validE | (keepE & 0x00800080u);
+            kminO = ~validO | (keepO & 0x00800080u);
+            kmaxE = ~validE | (keepE & 0x007F007Fu);
+            kmaxO = ~validO | (keepO & 0x007F007Fu);
+        }
+        if (r % P == P - 1) flush(rowpos >> 7);
+    }
+    const uint32_t bytes = (rowpos + 7) / 8;
+    flush((bytes + 15) / 16);
+    if (active && xl == 0) sizes[d.sizes_base + k] = bytes;
+}
+
+template <int N>
+__global__ __launch_bounds__(192) void l3_encode_strip_kernel(const L3EncodeDesc* __restrict__ descs,
+                                                              uint32_t* __restrict__ sizes,
+                                                              uint8_t* __restrict__ slots) {
+    __shared__ __attribute__((aligned(16))) uint32_t rings[3][StripGeom<N>::TPW * StripGeom<N>::RING / 4];
+    const L3EncodeDesc& d = descs[blockIdx.y];
+    if (d.patch != N || blockIdx.x >= d.strips_x * d.tiles_y) return;
+    const uint32_t c = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (c == 0) encode_strip<N, 0>(d, sizes, slots, rings[0]);
+    else if (c == 1) encode_strip<N, 1>(d, sizes, slots, rings[1]);
+    else encode_strip<N, 2>(d, sizes, slots, rings[2]);
+}
+
+/* Copies every slot of the strip route to its place in the file. */
+__global__ __launch_bounds__(256) void l3_encode_compact_kernel(const L3EncodeDesc* __restrict__ descs,
+                                                                const uint32_t* __restrict__ sizes,
+                                                                const uint8_t* __restrict__ slots,
+                                                                const uint64_t* __restrict__ file_len) {
+    const L3EncodeDesc& d = descs[blockIdx.y];
+    const uint32_t patches = d.tiles_x * d.tiles_y;
+    const uint32_t k = blockIdx.x;
+    if ((d.patch != 32 && d.patch != 64 && d.patch != 128) || k >= 3 * patches) return;
+    const uint64_t need = file_len[d.status_index];
+    if (need > d.file_cap || need - (13 + 12ull * patches) > 0xFFFFFFFFull) return;
+    const uint32_t bytes = sizes[d.sizes_base + k];
+    const uint32_t offset = *reinterpret_cast<const global_u32_unaligned*>((uintptr_t)(d.file + 13 + 4 * (size_t)k));
+    const uint8_t* from = slots + d.slots_base + (uint64_t)k * strip_slot_bytes(d.patch);
+    uint8_t* to = d.file + 13 + 12 * (size_t)patches + offset;
+    typedef __attribute__((address_space(1))) u32x4 global_u32x4_any __attribute__((aligned(1)));
+    const uint32_t whole = bytes / 16;
+    for (uint32_t i = threadIdx.x; i < whole; i += 256)
+        *reinterpret_cast<global_u32x4_any*>((uintptr_t)(to + 16 * (size_t)i)) =
+            *reinterpret_cast<const global_const_u32x4*>((uintptr_t)(from + 16 * (size_t)i));
+    const uint32_t tail = bytes - 16 * whole;
+    if (threadIdx.x < tail) to[16 * (size_t)whole + threadIdx.x] = from[16 * (size_t)whole + threadIdx.x];
+}
+
+/* ---- the plain route: any other N up to 128 -------------------------------- */
+
 __global__ __launch_bounds__(64) void l3_encode_measure_kernel(const L3EncodeDesc* __restrict__ descs,
                                                                uint32_t* __restrict__ sizes) {
     const L3EncodeDesc& d = descs[blockIdx.y];
     const uint32_t patches = d.tiles_x * d.tiles_y;
     const uint32_t k = blockIdx.x;
-    if (k >= 3 * patches) return;
+    if (k >= 3 * patches || d.patch == 32 || d.patch == 64 || d.patch == 128) return;
     const uint32_t c = k / patches, i = k - c * patches;
     const uint32_t bits = walk_patch<false>(d, c, i % d.tiles_x, i / d.tiles_x, nullptr);
     if (threadIdx.x == 0) sizes[d.sizes_base + k] = (bits + 7) / 8;
@@ -211,7 +483,7 @@ __global__ __launch_bounds__(64) void l3_encode_pack_kernel(const L3EncodeDesc* 
     const L3EncodeDesc& d = descs[blockIdx.y];
     const uint32_t patches = d.tiles_x * d.tiles_y;
     const uint32_t k = blockIdx.x;
-    if (k >= 3 * patches) return;
+    if (k >= 3 * patches || d.patch == 32 || d.patch == 64 || d.patch == 128) return;
     const uint64_t need = file_len[d.status_index];
     if (need > d.file_cap || need - (13 + 12ull * patches) > 0xFFFFFFFFull) return;
 
@@ -242,6 +514,8 @@ struct L3EncodeState {
     size_t desc_cap = 0;
     uint32_t* d_sizes = nullptr;
     size_t sizes_cap = 0;
+    uint8_t* d_slots = nullptr;      /* strip route: one fixed-size slot per patch and channel */
+    size_t slots_cap = 0;
     hipEvent_t done = nullptr;
     bool pending = false;
 };
@@ -253,6 +527,7 @@ void l3_encode_state_free(L3EncodeState* s) {
     if (s->h_descs) (void)hipHostFree(s->h_descs);
     if (s->d_descs) (void)hipFree(s->d_descs);
     if (s->d_sizes) (void)hipFree(s->d_sizes);
+    if (s->d_slots) (void)hipFree(s->d_slots);
     delete s;
 }
 
@@ -264,8 +539,10 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return L3_ERR_DEVICE;
 
-    size_t total_patches = 0;
+    size_t total_patches = 0, slot_bytes = 0;
     uint32_t max_patches = 0, max_n = 1;
+    uint32_t strip_units[3] = {0, 0, 0};   /* largest grid of the strip route per N = 32, 64, 128 */
+    bool any_plain = false;
     for (int i = 0; i < n; ++i) {
         const l3_encode_item& it = items[i];
         if (!it.d_rgb || !it.d_file || it.width == 0 || it.height == 0 ||
@@ -279,6 +556,15 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
         if (3 * p > 0x7FFFFFFFull) return L3_ERR_UNSUPPORTED;
         total_patches += (size_t)(3 * p);
         if (3 * p > max_patches) max_patches = (uint32_t)(3 * p);
+        if (np == 32 || np == 64 || np == 128) {
+            const uint32_t cls = np == 32 ? 0 : np == 64 ? 1 : 2;
+            const uint32_t tpw = 256 / np, tiles_x = (it.width + np - 1) / np;
+            const uint64_t units = (uint64_t)((tiles_x + tpw - 1) / tpw) * ((it.height + np - 1) / np);
+            if (units > strip_units[cls]) strip_units[cls] = (uint32_t)units;
+            slot_bytes += (size_t)(3 * p) * strip_slot_bytes(np);
+        } else {
+            any_plain = true;
+        }
     }
     if (total_patches > 0xFFFFFFFFull) return L3_ERR_UNSUPPORTED;
 
@@ -317,7 +603,16 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
         st->sizes_cap = cap;
     }
 
-    size_t base = 0;
+    if (slot_bytes > st->slots_cap) {
+        if (st->d_slots) (void)hipFree(st->d_slots);
+        st->d_slots = nullptr;
+        st->slots_cap = 0;
+        if (hipMalloc(reinterpret_cast<void**>(&st->d_slots), slot_bytes) != hipSuccess)
+            return L3_ERR_DEVICE;
+        st->slots_cap = slot_bytes;
+    }
+
+    size_t base = 0, slots_base = 0;
     for (int i = 0; i < n; ++i) {
         const l3_encode_item& it = items[i];
         L3EncodeDesc& d = st->h_descs[i];
@@ -333,24 +628,48 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
         d.patch = np;
         d.sizes_base = (uint32_t)base;
         d.status_index = (uint32_t)i;
-        d.pad_ = 0;
+        d.strips_x = 0;
+        d.slots_base = 0;
+        if (np == 32 || np == 64 || np == 128) {
+            const uint32_t tpw = 256 / np;
+            d.strips_x = (d.tiles_x + tpw - 1) / tpw;
+            d.slots_base = slots_base;
+            slots_base += 3 * (size_t)d.tiles_x * d.tiles_y * strip_slot_bytes(np);
+        }
         base += 3 * (size_t)d.tiles_x * d.tiles_y;
     }
     if (hipMemcpyAsync(st->d_descs, st->h_descs, (size_t)n * sizeof(L3EncodeDesc), hipMemcpyHostToDevice,
                        stream) != hipSuccess)
         return L3_ERR_DEVICE;
+    const bool any_strip = strip_units[0] || strip_units[1] || strip_units[2];
+    const size_t lds_bytes = ((size_t)max_n * (12 + 8 * (size_t)max_n) + 31) / 32 * 4 + 8;
     for (int first = 0; first < n; first += 65535) {
-        const int m = n - first < 65535 ? n - first : 65535;
-        hipLaunchKernelGGL(l3_encode_measure_kernel, dim3(max_patches, (uint32_t)m), dim3(64), 0, stream,
-                           st->d_descs + first, st->d_sizes);
+        const uint32_t m = (uint32_t)(n - first < 65535 ? n - first : 65535);
+        const L3EncodeDesc* dd = st->d_descs + first;
+        if (strip_units[0])
+            hipLaunchKernelGGL(l3_encode_strip_kernel<32>, dim3(strip_units[0], m), dim3(192), 0, stream, dd,
+                               st->d_sizes, st->d_slots);
+        if (strip_units[1])
+            hipLaunchKernelGGL(l3_encode_strip_kernel<64>, dim3(strip_units[1], m), dim3(192), 0, stream, dd,
+                               st->d_sizes, st->d_slots);
+        if (strip_units[2])
+            hipLaunchKernelGGL(l3_encode_strip_kernel<128>, dim3(strip_units[2], m), dim3(192), 0, stream, dd,
+                               st->d_sizes, st->d_slots);
+        if (any_plain)
+            hipLaunchKernelGGL(l3_encode_measure_kernel, dim3(max_patches, m), dim3(64), 0, stream, dd,
+                               st->d_sizes);
     }
     hipLaunchKernelGGL(l3_encode_layout_kernel, dim3((uint32_t)n), dim3(256), 0, stream, st->d_descs,
                        st->d_sizes, d_file_len, d_status);
-    const size_t lds_bytes = ((size_t)max_n * (12 + 8 * (size_t)max_n) + 31) / 32 * 4 + 8;
     for (int first = 0; first < n; first += 65535) {
-        const int m = n - first < 65535 ? n - first : 65535;
-        hipLaunchKernelGGL(l3_encode_pack_kernel, dim3(max_patches, (uint32_t)m), dim3(64), lds_bytes,
-                           stream, st->d_descs + first, st->d_sizes, d_file_len);
+        const uint32_t m = (uint32_t)(n - first < 65535 ? n - first : 65535);
+        const L3EncodeDesc* dd = st->d_descs + first;
+        if (any_strip)
+            hipLaunchKernelGGL(l3_encode_compact_kernel, dim3(max_patches, m), dim3(256), 0, stream, dd,
+                               st->d_sizes, st->d_slots, d_file_len);
+        if (any_plain)
+            hipLaunchKernelGGL(l3_encode_pack_kernel, dim3(max_patches, m), dim3(64), lds_bytes, stream, dd,
+                               st->d_sizes, d_file_len);
     }
     if (hipGetLastError() != hipSuccess) return L3_ERR_DEVICE;
     if (hipEventRecord(st->done, stream) != hipSuccess) return L3_ERR_DEVICE;

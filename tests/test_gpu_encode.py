@@ -115,6 +115,33 @@ def test_degenerate_content(l3, ctx):
         check(l3, ctx, images, patch=patch)
 
 
+@pytest.mark.parametrize("patch", [32, 64, 128])
+def test_last_patch_one_to_nine_pixels_wide(l3, ctx, patch):
+    """The last patch of a row is 1..9 pixels wide and the strip has unused lanes: every
+    residue of the width modulo 4, one-column patches, patches that end inside a lane."""
+    images = [synth.voronoi_scene(2100 + k, 2 * patch + k, 37 + k, sites=5) for k in range(1, 10)]
+    images += [synth.uniform_bytes(2200 + k, k, 5) for k in range(1, 6)]
+    check(l3, ctx, images, patch=patch, pad_cols=3)
+
+
+def test_rows_of_every_width(l3, ctx):
+    """Row r of each patch carries noise of amplitude 2^(r % 10) - 1, so that every delta
+    width from 0 to 8 occurs, next to rows that wrap modulo 256."""
+    h, w = 150, 300
+    rng = np.random.default_rng(77)
+    img = np.zeros((h, w, 3), np.uint8)
+    for r in range(h):
+        amp = (1 << (r % 10)) - 1
+        img[r] = (100 + rng.integers(0, amp + 1, size=(w, 3))) % 256
+    for patch in (32, 64, 128):
+        check(l3, ctx, [img], patch=patch)
+
+
+def test_both_routes_in_one_call(l3, ctx):
+    images = [synth.cosine_field(2300 + k, 260 + 3 * k, 140 + k) for k in range(6)]
+    check(l3, ctx, images, patch=[128, 7, 32, 100, 64, 33])
+
+
 def test_benchmark_configurations(l3, ctx):
     """Default patch rule on the benchmark shapes: a slice of the photo-sized batch, two
     street-scene images, one compressible and one incompressible 3840x2160 image."""
