@@ -190,8 +190,12 @@ typedef struct {
  *               data; nothing is written beyond file_cap); bit 1 = encoded data
  *               beyond 4 GiB (not representable in the format's 32-bit offsets).
  *   stream      a hipStream_t; the call returns after enqueueing.  Calls on one
- *               context reuse one workspace: a second call waits (on the host) for
- *               the kernels of the first.
+ *               context share one workspace: on the device a call runs after the
+ *               kernels of the previous one, whatever their streams; the host
+ *               waits for them only when the workspace has to grow (batches of
+ *               more than 32 images, or with a patch size other than 32, 64, 128,
+ *               go through a ring of four pinned descriptor tables, so the host
+ *               can run at most four such calls ahead of the device).
  * Patch sizes above 128 give UNSUPPORTED.  Errors are synchronous: INVALID_ARG,
  * UNSUPPORTED, DEVICE (a HIP call failed; some kernels may have been enqueued). */
 l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, int n,

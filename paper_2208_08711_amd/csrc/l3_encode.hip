@@ -161,6 +161,7 @@ struct StripGeom {
     static constexpr int P = 3;                    /* rows between two flushes of the rings */
     static constexpr int ROW_MAX = N + 3;          /* bytes a row can touch: ceil((12 + 8N)/8) + 1 */
     static constexpr int RING = 8 * N;             /* ring bytes per patch and channel */
+    static constexpr int RING_WORDS = RING / 4 + 4; /* + a word that stands for word 0 of the next lap (and padding to 16 bytes) */
     /* the longest patch stream, rounded up to whole 16-byte granules */
     static constexpr uint32_t SLOT = ((uint32_t)N * (12 + 8 * N) / 8 + 1 + 15) / 16 * 16;
     /* one flush round (a granule per lane of the patch) takes everything that P rows
@@ -188,7 +189,8 @@ __device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
 }
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+    /* every lane has a source lane under these controls, so the "old" value is never used */
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 
 /* Minimum of both 16-bit fields, separately, over the LPT lanes of a patch; every
@@ -229,7 +231,7 @@ __device__ __forceinline__ void encode_strip(const L3EncodeDesc& d, uint32_t* __
     /* this lane's 4 pixels: columns 4 xl .. 4 xl + 3 of the patch, nvalid of them exist */
     const uint32_t xpix = 4 * xl;
     const uint32_t nvalid = pw > xpix ? min(4u, pw - xpix) : 0u;
-    const uint8_t* src = d.rgb + (size_t)y0 * d.row_stride + ((size_t)x0 + xpix) * 3;
+    const uint8_t* src = d.rgb + (size_t)y0 * d.row_stride + ((size_t)x0 + xpix) * 3;   /* walks down the rows */
 
     /* registers of two 16-bit fields: E = pixels (0, 2), O = pixels (1, 3) */
     const uint32_t validE = (nvalid > 0 ? 0x0000FFFFu : 0u) | (nvalid > 2 ? 0xFFFF0000u : 0u);
@@ -247,15 +249,35 @@ __device__ __forceinline__ void encode_strip(const L3EncodeDesc& d, uint32_t* __
     uint32_t kmaxE = ~validE | keepE, kmaxO = ~validO | keepO;          /* K ^ 0xFF = 0xFF */
     uint32_t krow = 0;
 
-    auto load_row = [&](uint32_t r) -> u32x3 {
+    uint64_t row_stride = d.row_stride;
+    asm volatile("" : "+s"(row_stride));    /* kept in registers, not reloaded every row */
+    /* The lane's 12 bytes of a row.  A lane at the right edge of the image owns fewer than
+     * 4 pixels and must not read past the row: it reads the 12 bytes that END at its last
+     * pixel and shifts them down (what then sits above the valid bytes is masked later).
+     * Only waves with such a lane take that path; images narrower than 4 pixels go byte by
+     * byte. */
+    const bool ragged_wave = __builtin_amdgcn_ballot_w64(nvalid != 0 && nvalid != 4) != 0;
+    const bool wide = d.width >= 4;
+    const uint32_t back = nvalid ? 3 * (4 - nvalid) : 0;              /* bytes to step back: 0, 3, 6, 9 */
+    auto load_row = [&](const uint8_t* p) -> u32x3 {
         u32x3 v = {0, 0, 0};
-        const uint8_t* p = src + (size_t)r * d.row_stride;
-        if (nvalid == 4) {
-            v = *reinterpret_cast<global_const_u32x3_any*>((uintptr_t)p);
+        if (!ragged_wave) {
+            if (nvalid == 4) v = *reinterpret_cast<global_const_u32x3_any*>((uintptr_t)p);
+        } else if (wide) {
+            if (nvalid) {
+                const u32x3 q = *reinterpret_cast<global_const_u32x3_any*>((uintptr_t)(p - back));
+                const uint32_t words = back >> 2, bits = (back & 3u) * 8;
+                const uint32_t a0 = words == 0 ? q.x : (words == 1 ? q.y : q.z);
+                const uint32_t a1 = words == 0 ? q.y : (words == 1 ? q.z : 0u);
+                const uint32_t a2 = words == 0 ? q.z : 0u;
+                v.x = __builtin_amdgcn_alignbit(a1, a0, bits);
+                v.y = __builtin_amdgcn_alignbit(a2, a1, bits);
+                v.z = a2 >> bits;
+            }
         } else if (nvalid) {
-            uint32_t b[12];
+            uint32_t b[9];
 #pragma unroll
-            for (int i = 0; i < 12; ++i) b[i] = (uint32_t)(i < 9 && (uint32_t)i < 3 * nvalid ? p[i] : 0);
+            for (int i = 0; i < 9; ++i) b[i] = (uint32_t)((uint32_t)i < 3 * nvalid ? p[i] : 0);
             v.x = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
             v.y = b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24);
             v.z = b[8];
@@ -263,25 +285,25 @@ __device__ __forceinline__ void encode_strip(const L3EncodeDesc& d, uint32_t* __
         return v;
     };
 
-    uint32_t* const ring = ring_words + g * (RING / 4);
+    uint32_t* const ring = ring_words + g * G::RING_WORDS;
     const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)ring;
     typedef __attribute__((address_space(3))) uint32_t lds_u32;
-    constexpr uint32_t WM = RING / 4 - 1;
     {
         u32x4 zero = {0, 0, 0, 0};
-        for (uint32_t i = xl; i < RING / 16; i += LPT) reinterpret_cast<u32x4*>(ring)[i] = zero;
+        for (uint32_t i = xl; i < G::RING_WORDS / 4; i += LPT) reinterpret_cast<u32x4*>(ring)[i] = zero;
     }
     wave_lds_fence();
 
-    /* ORs `nbits`-wide `value` (at most 32 bits) into the ring at bit `pos` */
+    /* ORs `value` (at most 32 bits) into the ring at bit `pos`.  The upper part may land in
+     * the word behind the ring, which stands for word 0 of the next lap: the flush folds
+     * it in. */
     auto put = [&](uint32_t value, uint32_t pos) {
-        const uint32_t w0 = (pos >> 5) & WM, w1 = (w0 + 1) & WM;
+        const uint32_t w0 = __builtin_amdgcn_ubfe(pos, 5, __builtin_ctz(RING / 4));
         const uint32_t lo = value << (pos & 31u);
         const uint32_t hi = (value >> 1) >> (~pos & 31u);
-        __hip_atomic_fetch_or(reinterpret_cast<lds_u32*>(ring_lds + 4 * w0), lo, __ATOMIC_RELAXED,
-                              __HIP_MEMORY_SCOPE_WAVEFRONT);
-        __hip_atomic_fetch_or(reinterpret_cast<lds_u32*>(ring_lds + 4 * w1), hi, __ATOMIC_RELAXED,
-                              __HIP_MEMORY_SCOPE_WAVEFRONT);
+        lds_u32* cell = reinterpret_cast<lds_u32*>(ring_lds + 4 * w0);
+        __hip_atomic_fetch_or(cell, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        __hip_atomic_fetch_or(cell + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
     };
 
     uint32_t rowpos = 0;       /* bit position of the next row record in the patch stream */
@@ -291,10 +313,15 @@ __device__ __forceinline__ void encode_strip(const L3EncodeDesc& d, uint32_t* __
         wave_lds_fence();
         const uint32_t gi = flushed + xl;
         if (active && gi < upto) {
-            u32x4* cell = reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + ((gi * 16) & (RING - 1)));
-            const u32x4 v = *cell;
+            const uint32_t at = (gi * 16) & (RING - 1);
+            u32x4* cell = reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + at);
+            u32x4 v = *cell;
             const u32x4 zero = {0, 0, 0, 0};
             *cell = zero;
+            if (at == 0) {                  /* what the previous lap left for this granule's first word */
+                v.x |= ring[RING / 4];
+                ring[RING / 4] = 0;
+            }
             *reinterpret_cast<global_u32x4*>((uintptr_t)(slot + (size_t)gi * 16)) = v;
         }
         flushed = max(flushed, upto);
@@ -302,11 +329,10 @@ __device__ __forceinline__ void encode_strip(const L3EncodeDesc& d, uint32_t* __
     };
 
     uint32_t up[2] = {0, 0};   /* the original row above; zeros above the first row predict 0 */
-    u32x3 next = load_row(0);
-    for (uint32_t r = 0; r < ph; ++r) {
-        const u32x3 raw = next;
-        if (r + 1 < ph) next = load_row(r + 1);
 
+    /* One row: filter, row minimum and maximum, the lane's deltas into the ring.  Returns
+     * the row's 12-bit record; its place is the value of rowpos on entry. */
+    auto do_row = [&](const u32x3 raw) -> uint32_t {
         /* channel C of pixel i is byte 3 i + C of the lane's 12 bytes */
         uint32_t cur[2];
         if (C == 0) {
@@ -355,22 +381,55 @@ __device__ __forceinline__ void encode_strip(const L3EncodeDesc& d, uint32_t* __
         const uint32_t dE = pk_sub_u16_sat(top, uE), dO = pk_sub_u16_sat(top, uO);
         const uint32_t pair = dE | (dO << w);                   /* (d0 | d1 << w, d2 | d3 << w) */
         const uint32_t group = (pair & 0xFFFFu) | ((pair >> 16) << (2 * w));
-        if (active) {
-            put(group, rowpos + 12 + xpix * w);
-            if (xl == 0) put(rec, rowpos);
-        }
+        if (active) put(group, rowpos + 12 + xpix * w);
         rowpos += 12 + pw * w;
-
         up[0] = cur[0];
         up[1] = cur[1];
-        if (r == 0) {
+        return rec;
+    };
+
+    /* Periods of P rows.  The rows of the next period are already travelling from memory
+     * while this one is worked on; the granules the previous period completed are written
+     * out right after those loads were issued, so that neither is waited for before a
+     * whole period of arithmetic has passed. */
+    u32x3 ahead[P];
+#pragma unroll
+    for (int i = 0; i < P; ++i) {
+        const u32x3 zero = {0, 0, 0};
+        ahead[i] = (uint32_t)i < ph ? load_row(src + i * row_stride) : zero;
+    }
+    for (uint32_t r = 0; r < ph; r += P) {
+        const uint32_t rows = min((uint32_t)P, ph - r);
+        u32x3 raw[P];
+#pragma unroll
+        for (int i = 0; i < P; ++i) raw[i] = ahead[i];
+        src += P * row_stride;
+        if (r + P < ph) {
+#pragma unroll
+            for (int i = 0; i < P; ++i)
+                if (r + P + i < ph) ahead[i] = load_row(src + i * row_stride);
+        }
+        if (r > 0) flush(rowpos >> 7);
+
+        uint32_t rec[P], at[P];
+        at[0] = rowpos;
+        rec[0] = do_row(raw[0]);
+        if (r == 0) {            /* rows after the first are looked at as signed bytes */
             krow = 0x80u;
             kminE = ~validE | (keepE & 0x00800080u);
             kminO = ~validO | (keepO & 0x00800080u);
             kmaxE = ~validE | (keepE & 0x007F007Fu);
             kmaxO = ~validO | (keepO & 0x007F007Fu);
         }
-        if (r % P == P - 1) flush(rowpos >> 7);
+        at[1] = rowpos;
+        rec[1] = rows > 1 ? do_row(raw[1]) : 0u;
+        at[2] = rowpos;
+        rec[2] = rows > 2 ? do_row(raw[2]) : 0u;
+        /* the records of the period: lane i of the patch writes the one of row i */
+        static_assert(P == 3 && LPT >= P, "one lane per record of a period");
+        const uint32_t my_rec = xl == 0 ? rec[0] : (xl == 1 ? rec[1] : rec[2]);
+        const uint32_t my_at = xl == 0 ? at[0] : (xl == 1 ? at[1] : at[2]);
+        if (active && xl < rows) put(my_rec, my_at);
     }
     const uint32_t bytes = (rowpos + 7) / 8;
     flush((bytes + 15) / 16);
@@ -378,11 +437,9 @@ __device__ __forceinline__ void encode_strip(const L3EncodeDesc& d, uint32_t* __
 }
 
 template <int N>
-__global__ __launch_bounds__(192) void l3_encode_strip_kernel(const L3EncodeDesc* __restrict__ descs,
-                                                              uint32_t* __restrict__ sizes,
-                                                              uint8_t* __restrict__ slots) {
-    __shared__ __attribute__((aligned(16))) uint32_t rings[3][StripGeom<N>::TPW * StripGeom<N>::RING / 4];
-    const L3EncodeDesc& d = descs[blockIdx.y];
+__device__ __forceinline__ void strip_block(const L3EncodeDesc& d, uint32_t* __restrict__ sizes,
+                                            uint8_t* __restrict__ slots) {
+    __shared__ __attribute__((aligned(16))) uint32_t rings[3][StripGeom<N>::TPW * StripGeom<N>::RING_WORDS];
     if (d.patch != N || blockIdx.x >= d.strips_x * d.tiles_y) return;
     const uint32_t c = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (c == 0) encode_strip<N, 0>(d, sizes, slots, rings[0]);
@@ -390,12 +447,30 @@ __global__ __launch_bounds__(192) void l3_encode_strip_kernel(const L3EncodeDesc
     else encode_strip<N, 2>(d, sizes, slots, rings[2]);
 }
 
-/* Copies every slot of the strip route to its place in the file. */
-__global__ __launch_bounds__(256) void l3_encode_compact_kernel(const L3EncodeDesc* __restrict__ descs,
-                                                                const uint32_t* __restrict__ sizes,
-                                                                const uint8_t* __restrict__ slots,
-                                                                const uint64_t* __restrict__ file_len) {
-    const L3EncodeDesc& d = descs[blockIdx.y];
+/* Descriptors either in a device table (any batch size) or, for small batches, inside
+ * the kernel arguments: no upload to wait for, so consecutive calls run back to back. */
+constexpr int kArgDescs = 32;
+struct EncodePack { L3EncodeDesc d[kArgDescs]; };
+static_assert(sizeof(EncodePack) + 64 <= 4096, "kernel argument segment");
+
+template <int N>
+__global__ __launch_bounds__(192) void l3_encode_strip_kernel(const L3EncodeDesc* __restrict__ descs,
+                                                              uint32_t* __restrict__ sizes,
+                                                              uint8_t* __restrict__ slots) {
+    strip_block<N>(descs[blockIdx.y], sizes, slots);
+}
+template <int N>
+__global__ __launch_bounds__(192) void l3_encode_strip_kernel_args(const EncodePack pack,
+                                                                   uint32_t* __restrict__ sizes,
+                                                                   uint8_t* __restrict__ slots) {
+    strip_block<N>(pack.d[blockIdx.y], sizes, slots);
+}
+
+/* Copies one slot of the strip route to its place in the file (one workgroup per slot). */
+template <int THREADS>
+__device__ __forceinline__ void compact_block(const L3EncodeDesc& d, const uint32_t* __restrict__ sizes,
+                                              const uint8_t* __restrict__ slots,
+                                              const uint64_t* __restrict__ file_len) {
     const uint32_t patches = d.tiles_x * d.tiles_y;
     const uint32_t k = blockIdx.x;
     if ((d.patch != 32 && d.patch != 64 && d.patch != 128) || k >= 3 * patches) return;
@@ -407,11 +482,25 @@ __global__ __launch_bounds__(256) void l3_encode_compact_kernel(const L3EncodeDe
     uint8_t* to = d.file + 13 + 12 * (size_t)patches + offset;
     typedef __attribute__((address_space(1))) u32x4 global_u32x4_any __attribute__((aligned(1)));
     const uint32_t whole = bytes / 16;
-    for (uint32_t i = threadIdx.x; i < whole; i += 256)
+    for (uint32_t i = threadIdx.x; i < whole; i += THREADS)
         *reinterpret_cast<global_u32x4_any*>((uintptr_t)(to + 16 * (size_t)i)) =
             *reinterpret_cast<const global_const_u32x4*>((uintptr_t)(from + 16 * (size_t)i));
     const uint32_t tail = bytes - 16 * whole;
     if (threadIdx.x < tail) to[16 * (size_t)whole + threadIdx.x] = from[16 * (size_t)whole + threadIdx.x];
+}
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void l3_encode_compact_kernel(const L3EncodeDesc* __restrict__ descs,
+                                                                    const uint32_t* __restrict__ sizes,
+                                                                    const uint8_t* __restrict__ slots,
+                                                                    const uint64_t* __restrict__ file_len) {
+    compact_block<THREADS>(descs[blockIdx.y], sizes, slots, file_len);
+}
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void l3_encode_compact_kernel_args(const EncodePack pack,
+                                                                         const uint32_t* __restrict__ sizes,
+                                                                         const uint8_t* __restrict__ slots,
+                                                                         const uint64_t* __restrict__ file_len) {
+    compact_block<THREADS>(pack.d[blockIdx.y], sizes, slots, file_len);
 }
 
 /* ---- the plain route: any other N up to 128 -------------------------------- */
@@ -428,11 +517,9 @@ __global__ __launch_bounds__(64) void l3_encode_measure_kernel(const L3EncodeDes
 }
 
 /* One workgroup per image: offsets = exclusive prefix sum of the patch sizes. */
-__global__ __launch_bounds__(256) void l3_encode_layout_kernel(const L3EncodeDesc* __restrict__ descs,
-                                                               const uint32_t* __restrict__ sizes,
-                                                               uint64_t* __restrict__ file_len,
-                                                               uint32_t* __restrict__ status) {
-    const L3EncodeDesc& d = descs[blockIdx.x];
+__device__ __forceinline__ void layout_block(const L3EncodeDesc& d, const uint32_t* __restrict__ sizes,
+                                             uint64_t* __restrict__ file_len,
+                                             uint32_t* __restrict__ status) {
     const uint32_t patches = d.tiles_x * d.tiles_y, total = 3 * patches;
     const uint64_t header = 13 + 12ull * patches;
     const bool header_fits = header <= d.file_cap;
@@ -476,6 +563,18 @@ __global__ __launch_bounds__(256) void l3_encode_layout_kernel(const L3EncodeDes
         }
     }
 }
+__global__ __launch_bounds__(256) void l3_encode_layout_kernel(const L3EncodeDesc* __restrict__ descs,
+                                                               const uint32_t* __restrict__ sizes,
+                                                               uint64_t* __restrict__ file_len,
+                                                               uint32_t* __restrict__ status) {
+    layout_block(descs[blockIdx.x], sizes, file_len, status);
+}
+__global__ __launch_bounds__(256) void l3_encode_layout_kernel_args(const EncodePack pack,
+                                                                    const uint32_t* __restrict__ sizes,
+                                                                    uint64_t* __restrict__ file_len,
+                                                                    uint32_t* __restrict__ status) {
+    layout_block(pack.d[blockIdx.x], sizes, file_len, status);
+}
 
 __global__ __launch_bounds__(64) void l3_encode_pack_kernel(const L3EncodeDesc* __restrict__ descs,
                                                             const uint32_t* __restrict__ sizes,
@@ -509,21 +608,27 @@ __global__ __launch_bounds__(64) void l3_encode_pack_kernel(const L3EncodeDesc* 
 
 /* Workspace of l3_encode_batch: descriptor table (pinned + device) and patch sizes. */
 struct L3EncodeState {
-    L3EncodeDesc* h_descs = nullptr;
+    L3EncodeDesc* h_descs = nullptr;  /* pinned: kStage staging tables of desc_cap entries each */
+    hipEvent_t staged[4] = {};        /* the upload from staging table i has left it */
+    bool staged_pending[4] = {};
+    int next_stage = 0;
     L3EncodeDesc* d_descs = nullptr;
     size_t desc_cap = 0;
     uint32_t* d_sizes = nullptr;
     size_t sizes_cap = 0;
     uint8_t* d_slots = nullptr;      /* strip route: one fixed-size slot per patch and channel */
     size_t slots_cap = 0;
-    hipEvent_t done = nullptr;
+    hipEvent_t done = nullptr;       /* the last call's kernels have finished */
     bool pending = false;
+    hipStream_t last_stream = nullptr;
 };
 
 void l3_encode_state_free(L3EncodeState* s) {
     if (!s) return;
     if (s->pending) (void)hipEventSynchronize(s->done);
     if (s->done) (void)hipEventDestroy(s->done);
+    for (int i = 0; i < 4; ++i)
+        if (s->staged[i]) (void)hipEventDestroy(s->staged[i]);
     if (s->h_descs) (void)hipHostFree(s->h_descs);
     if (s->d_descs) (void)hipFree(s->d_descs);
     if (s->d_sizes) (void)hipFree(s->d_sizes);
@@ -574,25 +679,49 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
         if (hipEventCreateWithFlags(&ctx->enc->done, hipEventDisableTiming) != hipSuccess) return L3_ERR_DEVICE;
     }
     L3EncodeState* st = ctx->enc;
-    if (st->pending) {   /* the workspace is reused: wait for the previous call's kernels */
-        if (hipEventSynchronize(st->done) != hipSuccess) return L3_ERR_DEVICE;
+    /* The workspace (size table, slots, descriptor table) is shared by consecutive calls.
+     * On the device a call is ordered after the previous one; the host waits for the
+     * previous call only before it frees or overwrites something that call still reads. */
+    auto wait_previous = [&]() -> bool {
+        if (st->pending && hipEventSynchronize(st->done) != hipSuccess) return false;
         st->pending = false;
-    }
-    if ((size_t)n > st->desc_cap) {
-        size_t cap = 64;
-        while (cap < (size_t)n) cap *= 2;
-        if (st->h_descs) (void)hipHostFree(st->h_descs);
-        if (st->d_descs) (void)hipFree(st->d_descs);
-        st->h_descs = nullptr;
-        st->d_descs = nullptr;
-        st->desc_cap = 0;
-        if (hipHostMalloc(reinterpret_cast<void**>(&st->h_descs), cap * sizeof(L3EncodeDesc),
-                          hipHostMallocDefault) != hipSuccess ||
-            hipMalloc(reinterpret_cast<void**>(&st->d_descs), cap * sizeof(L3EncodeDesc)) != hipSuccess)
+        return true;
+    };
+    if (st->pending && stream != st->last_stream &&
+        hipStreamWaitEvent(stream, st->done, 0) != hipSuccess)
+        return L3_ERR_DEVICE;
+    const bool by_args = n <= kArgDescs && !any_plain;
+    constexpr int kStage = 4;
+    int stage = 0;
+    if (!by_args) {
+        if ((size_t)n > st->desc_cap) {
+            if (!wait_previous()) return L3_ERR_DEVICE;      /* its uploads and kernels read the old tables */
+            size_t cap = 64;
+            while (cap < (size_t)n) cap *= 2;
+            if (st->h_descs) (void)hipHostFree(st->h_descs);
+            if (st->d_descs) (void)hipFree(st->d_descs);
+            st->h_descs = nullptr;
+            st->d_descs = nullptr;
+            st->desc_cap = 0;
+            for (int i = 0; i < kStage; ++i) st->staged_pending[i] = false;
+            if (hipHostMalloc(reinterpret_cast<void**>(&st->h_descs), kStage * cap * sizeof(L3EncodeDesc),
+                              hipHostMallocDefault) != hipSuccess ||
+                hipMalloc(reinterpret_cast<void**>(&st->d_descs), cap * sizeof(L3EncodeDesc)) != hipSuccess)
+                return L3_ERR_DEVICE;
+            st->desc_cap = cap;
+        }
+        /* the staging table about to be rewritten: its last upload must have left it */
+        stage = st->next_stage;
+        st->next_stage = (stage + 1) % kStage;
+        if (!st->staged[stage] &&
+            hipEventCreateWithFlags(&st->staged[stage], hipEventDisableTiming) != hipSuccess)
             return L3_ERR_DEVICE;
-        st->desc_cap = cap;
+        if (st->staged_pending[stage] && hipEventSynchronize(st->staged[stage]) != hipSuccess)
+            return L3_ERR_DEVICE;
+        st->staged_pending[stage] = false;
     }
     if (total_patches > st->sizes_cap) {
+        if (!wait_previous()) return L3_ERR_DEVICE;
         size_t cap = 4096;
         while (cap < total_patches) cap *= 2;
         if (st->d_sizes) (void)hipFree(st->d_sizes);
@@ -602,8 +731,8 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
             return L3_ERR_DEVICE;
         st->sizes_cap = cap;
     }
-
     if (slot_bytes > st->slots_cap) {
+        if (!wait_previous()) return L3_ERR_DEVICE;
         if (st->d_slots) (void)hipFree(st->d_slots);
         st->d_slots = nullptr;
         st->slots_cap = 0;
@@ -612,10 +741,12 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
         st->slots_cap = slot_bytes;
     }
 
+    EncodePack pack;
+    L3EncodeDesc* const table = by_args ? pack.d : st->h_descs + (size_t)stage * st->desc_cap;
     size_t base = 0, slots_base = 0;
     for (int i = 0; i < n; ++i) {
         const l3_encode_item& it = items[i];
-        L3EncodeDesc& d = st->h_descs[i];
+        L3EncodeDesc& d = table[i];
         const uint32_t np = it.patch ? it.patch : l3_default_patch(it.width, it.height);
         d.rgb = it.d_rgb;
         d.file = it.d_file;
@@ -638,41 +769,70 @@ extern "C" l3_status l3_encode_batch(l3_ctx* ctx, const l3_encode_item* items, i
         }
         base += 3 * (size_t)d.tiles_x * d.tiles_y;
     }
-    if (hipMemcpyAsync(st->d_descs, st->h_descs, (size_t)n * sizeof(L3EncodeDesc), hipMemcpyHostToDevice,
-                       stream) != hipSuccess)
-        return L3_ERR_DEVICE;
-    const bool any_strip = strip_units[0] || strip_units[1] || strip_units[2];
-    const size_t lds_bytes = ((size_t)max_n * (12 + 8 * (size_t)max_n) + 31) / 32 * 4 + 8;
-    for (int first = 0; first < n; first += 65535) {
-        const uint32_t m = (uint32_t)(n - first < 65535 ? n - first : 65535);
-        const L3EncodeDesc* dd = st->d_descs + first;
+    if (by_args) {
+        for (int i = n; i < kArgDescs; ++i) std::memset(&pack.d[i], 0, sizeof(L3EncodeDesc));
+        const uint32_t m = (uint32_t)n;
         if (strip_units[0])
-            hipLaunchKernelGGL(l3_encode_strip_kernel<32>, dim3(strip_units[0], m), dim3(192), 0, stream, dd,
-                               st->d_sizes, st->d_slots);
+            hipLaunchKernelGGL(l3_encode_strip_kernel_args<32>, dim3(strip_units[0], m), dim3(192), 0, stream,
+                               pack, st->d_sizes, st->d_slots);
         if (strip_units[1])
-            hipLaunchKernelGGL(l3_encode_strip_kernel<64>, dim3(strip_units[1], m), dim3(192), 0, stream, dd,
-                               st->d_sizes, st->d_slots);
+            hipLaunchKernelGGL(l3_encode_strip_kernel_args<64>, dim3(strip_units[1], m), dim3(192), 0, stream,
+                               pack, st->d_sizes, st->d_slots);
         if (strip_units[2])
-            hipLaunchKernelGGL(l3_encode_strip_kernel<128>, dim3(strip_units[2], m), dim3(192), 0, stream, dd,
-                               st->d_sizes, st->d_slots);
-        if (any_plain)
-            hipLaunchKernelGGL(l3_encode_measure_kernel, dim3(max_patches, m), dim3(64), 0, stream, dd,
-                               st->d_sizes);
-    }
-    hipLaunchKernelGGL(l3_encode_layout_kernel, dim3((uint32_t)n), dim3(256), 0, stream, st->d_descs,
-                       st->d_sizes, d_file_len, d_status);
-    for (int first = 0; first < n; first += 65535) {
-        const uint32_t m = (uint32_t)(n - first < 65535 ? n - first : 65535);
-        const L3EncodeDesc* dd = st->d_descs + first;
-        if (any_strip)
-            hipLaunchKernelGGL(l3_encode_compact_kernel, dim3(max_patches, m), dim3(256), 0, stream, dd,
-                               st->d_sizes, st->d_slots, d_file_len);
-        if (any_plain)
-            hipLaunchKernelGGL(l3_encode_pack_kernel, dim3(max_patches, m), dim3(64), lds_bytes, stream, dd,
-                               st->d_sizes, d_file_len);
+            hipLaunchKernelGGL(l3_encode_strip_kernel_args<128>, dim3(strip_units[2], m), dim3(192), 0, stream,
+                               pack, st->d_sizes, st->d_slots);
+        hipLaunchKernelGGL(l3_encode_layout_kernel_args, dim3(m), dim3(256), 0, stream, pack, st->d_sizes,
+                           d_file_len, d_status);
+        /* a slot of a 128-pixel patch is up to 16.6 KB: four waves; smaller ones: one */
+        if (strip_units[2])
+            hipLaunchKernelGGL(l3_encode_compact_kernel_args<256>, dim3(max_patches, m), dim3(256), 0, stream,
+                               pack, st->d_sizes, st->d_slots, d_file_len);
+        else
+            hipLaunchKernelGGL(l3_encode_compact_kernel_args<64>, dim3(max_patches, m), dim3(64), 0, stream,
+                               pack, st->d_sizes, st->d_slots, d_file_len);
+    } else {
+        if (hipMemcpyAsync(st->d_descs, table, (size_t)n * sizeof(L3EncodeDesc), hipMemcpyHostToDevice,
+                           stream) != hipSuccess ||
+            hipEventRecord(st->staged[stage], stream) != hipSuccess)
+            return L3_ERR_DEVICE;
+        st->staged_pending[stage] = true;
+        const bool any_strip = strip_units[0] || strip_units[1] || strip_units[2];
+        const size_t lds_bytes = ((size_t)max_n * (12 + 8 * (size_t)max_n) + 31) / 32 * 4 + 8;
+        for (int first = 0; first < n; first += 65535) {
+            const uint32_t m = (uint32_t)(n - first < 65535 ? n - first : 65535);
+            const L3EncodeDesc* dd = st->d_descs + first;
+            if (strip_units[0])
+                hipLaunchKernelGGL(l3_encode_strip_kernel<32>, dim3(strip_units[0], m), dim3(192), 0, stream,
+                                   dd, st->d_sizes, st->d_slots);
+            if (strip_units[1])
+                hipLaunchKernelGGL(l3_encode_strip_kernel<64>, dim3(strip_units[1], m), dim3(192), 0, stream,
+                                   dd, st->d_sizes, st->d_slots);
+            if (strip_units[2])
+                hipLaunchKernelGGL(l3_encode_strip_kernel<128>, dim3(strip_units[2], m), dim3(192), 0, stream,
+                                   dd, st->d_sizes, st->d_slots);
+            if (any_plain)
+                hipLaunchKernelGGL(l3_encode_measure_kernel, dim3(max_patches, m), dim3(64), 0, stream, dd,
+                                   st->d_sizes);
+        }
+        hipLaunchKernelGGL(l3_encode_layout_kernel, dim3((uint32_t)n), dim3(256), 0, stream, st->d_descs,
+                           st->d_sizes, d_file_len, d_status);
+        for (int first = 0; first < n; first += 65535) {
+            const uint32_t m = (uint32_t)(n - first < 65535 ? n - first : 65535);
+            const L3EncodeDesc* dd = st->d_descs + first;
+            if (any_strip && strip_units[2])
+                hipLaunchKernelGGL(l3_encode_compact_kernel<256>, dim3(max_patches, m), dim3(256), 0, stream,
+                                   dd, st->d_sizes, st->d_slots, d_file_len);
+            else if (any_strip)
+                hipLaunchKernelGGL(l3_encode_compact_kernel<64>, dim3(max_patches, m), dim3(64), 0, stream,
+                                   dd, st->d_sizes, st->d_slots, d_file_len);
+            if (any_plain)
+                hipLaunchKernelGGL(l3_encode_pack_kernel, dim3(max_patches, m), dim3(64), lds_bytes, stream,
+                                   dd, st->d_sizes, d_file_len);
+        }
     }
     if (hipGetLastError() != hipSuccess) return L3_ERR_DEVICE;
     if (hipEventRecord(st->done, stream) != hipSuccess) return L3_ERR_DEVICE;
     st->pending = true;
+    st->last_stream = stream;
     return L3_OK;
 }
