@@ -264,13 +264,18 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
             const uint32_t pg = MODE == L3_MODE_HWC ? src[3 * q + 1] : src[QW + q];
             const uint32_t pb = MODE == L3_MODE_HWC ? src[3 * q + 2] : src[2 * QW + q];
             if (MODE == L3_MODE_HWC) {
-                uint8_t* dst = reinterpret_cast<uint8_t*>((uintptr_t)(out_base + (uint64_t)y * out_row_stride + (uint64_t)x * 3));
+                /* row start: scalar arithmetic; the lane's 32-bit column offset goes into the
+                 * store's offset register (kept opaque here so that it is not widened and
+                 * added with vector instructions ahead of time) */
+                uint32_t column = x * 3u;
+                asm volatile("" : "+v"(column));
+                global_u8* row = reinterpret_cast<global_u8*>((uintptr_t)(out_base + (uint64_t)y * out_row_stride));
                 const uint32_t o0 = pr, o1 = pg, o2 = pb;
                 if (nvalid == 4) {
                     const u32x3 v = {o0, o1, o2};
-                    __builtin_nontemporal_store(v, reinterpret_cast<global_u32x3_any*>((uintptr_t)dst));
+                    __builtin_nontemporal_store(v, reinterpret_cast<global_u32x3_any*>(row + column));
                 } else if (nvalid) {
-                    global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
+                    global_u8* b = row + column;
 #pragma unroll
                     for (int k = 0; k < 9; ++k) {
                         const uint32_t word = k < 4 ? o0 : (k < 8 ? o1 : o2);
@@ -281,11 +286,14 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
 #pragma unroll
                 for (int ch = 0; ch < 3; ++ch) {
                     const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
-                    uint8_t* dst = reinterpret_cast<uint8_t*>((uintptr_t)(out_base + (uint64_t)ch * out_plane_stride + (uint64_t)y * out_row_stride + x));
+                    global_u8* row = reinterpret_cast<global_u8*>(
+                        (uintptr_t)(out_base + (uint64_t)ch * out_plane_stride + (uint64_t)y * out_row_stride));
+                    uint32_t column = x;
+                    asm volatile("" : "+v"(column));
                     if (nvalid == 4) {
-                        __builtin_nontemporal_store(word, reinterpret_cast<global_u32_any*>((uintptr_t)dst));
+                        __builtin_nontemporal_store(word, reinterpret_cast<global_u32_any*>(row + column));
                     } else if (nvalid) {
-                        global_u8* b = reinterpret_cast<global_u8*>((uintptr_t)dst);
+                        global_u8* b = row + column;
 #pragma unroll
                         for (int k = 0; k < 3; ++k)
                             if ((uint32_t)k < nvalid) b[k] = (uint8_t)(word >> (8 * k));
