@@ -25,6 +25,9 @@ struct l3_ctx {
     L3ImageDesc* h_stage[kSlots] = {};    /* pinned host */
     L3ImageDesc* d_descs[kSlots] = {};    /* device */
     uint16_t* d_table[kSlots] = {};       /* device: 768-entry normalisation table */
+    float table_key[kSlots][7] = {};      /* mean, stdv, dtype the slot's table was built with */
+    bool table_valid[kSlots] = {};
+    hipStream_t table_stream[kSlots] = {};  /* stream that built it (another stream rebuilds) */
     hipEvent_t done[kSlots] = {};         /* the slot's kernels have finished */
     bool pending[kSlots] = {};
     int next = 0;

@@ -96,9 +96,12 @@ __device__ __forceinline__ uint32_t ring_align(RingWords v, uint32_t bit) {
     return __builtin_amdgcn_alignbit(v.hi, v.lo, bit);   /* ({hi,lo} >> (bit & 31)) */
 }
 
-__device__ __forceinline__ u32x4 load_granule(const uint8_t* p, const uint8_t* file_end16) {
+/* One 16-byte granule of a patch stream, zeros at and beyond `limit` (byte offsets from
+ * the stream's aligned origin): nothing is fetched past the granule that holds the
+ * stream's last byte. */
+__device__ __forceinline__ u32x4 load_granule(const uint8_t* origin, uint32_t at, uint32_t limit) {
     u32x4 v = {0, 0, 0, 0};
-    if (p < file_end16) v = *reinterpret_cast<global_const_u32x4*>((uintptr_t)p);
+    if (at < limit) v = *reinterpret_cast<global_const_u32x4*>((uintptr_t)(origin + at));
     return v;
 }
 
@@ -144,13 +147,11 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
         ph = min(ph, (uint32_t)d.crop_y0 + crop_h - y0);
     const uint32_t patches = d.tiles_x * d.tiles_y;
     const uint32_t data_len = (uint32_t)(d.file_len - d.header_bytes);
-    const uint8_t* file_end16 =
-        reinterpret_cast<const uint8_t*>(((uintptr_t)d.file + d.file_len + 15) & ~(uintptr_t)15);
 
     /* locate this lane group's stream: Section 4.3, offset array of channel c */
     uint32_t flags = 0;
-    uint32_t bitpos, endbit, fill;
-    const uint8_t* gaddr;
+    uint32_t bitpos, endbit, fill, limit;
+    const uint8_t* origin;
     u32x4 pf[GPL];
     uint32_t* const ring = rings[c][g];
     {
@@ -167,10 +168,11 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
         const uintptr_t ab = a & ~(uintptr_t)15;
         bitpos = (uint32_t)(a - ab) * 8;
         endbit = bitpos + (end - off) * 8;
-        gaddr = reinterpret_cast<const uint8_t*>(ab) + xl * 16;
+        origin = reinterpret_cast<const uint8_t*>(ab);
+        limit = ((endbit >> 3) + 15u) & ~15u;     /* the stream's granules end here; inside the file's last one */
         /* first chunk into the ring (covers the first period), second into registers */
 #pragma unroll
-        for (int t = 0; t < GPL; ++t) pf[t] = load_granule(gaddr + t * LPT * 16, file_end16);
+        for (int t = 0; t < GPL; ++t) pf[t] = load_granule(origin, (t * LPT + xl) * 16, limit);
 #pragma unroll
         for (int t = 0; t < GPL; ++t) {
             const uint32_t idx = (t * LPT + xl) * 16;
@@ -179,7 +181,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
         }
         fill = CHUNK;
 #pragma unroll
-        for (int t = 0; t < GPL; ++t) pf[t] = load_granule(gaddr + CHUNK + t * LPT * 16, file_end16);
+        for (int t = 0; t < GPL; ++t) pf[t] = load_granule(origin, CHUNK + (t * LPT + xl) * 16, limit);
     }
     wave_lds_fence();
 
@@ -464,7 +466,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                     fill += CHUNK;
 #pragma unroll
                     for (int t = 0; t < GPL; ++t)
-                        pf[t] = load_granule(gaddr + fill + t * LPT * 16, file_end16);
+                        pf[t] = load_granule(origin, fill + (t * LPT + xl) * 16, limit);
                 }
                 wave_lds_fence();
             }
@@ -769,8 +771,18 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     }
     const uint16_t* table = nullptr;
     if (mode == L3_MODE_TENSOR) {
-        hipLaunchKernelGGL(l3_build_table_kernel, dim3(3), dim3(256), 0, stream, mean[0], mean[1],
-                           mean[2], stdv[0], stdv[1], stdv[2], dtype, ctx->d_table[slot]);
+        /* The slot's table is rebuilt only when the constants differ from the ones it was
+         * built with (the slot's earlier kernels have finished: waited for above).  The
+         * build runs on this call's stream, ahead of the kernel that reads the table. */
+        const float key[7] = {mean[0], mean[1], mean[2], stdv[0], stdv[1], stdv[2], (float)dtype};
+        if (!ctx->table_valid[slot] || std::memcmp(ctx->table_key[slot], key, sizeof key) != 0 ||
+            ctx->table_stream[slot] != stream) {
+            hipLaunchKernelGGL(l3_build_table_kernel, dim3(3), dim3(256), 0, stream, mean[0], mean[1],
+                               mean[2], stdv[0], stdv[1], stdv[2], dtype, ctx->d_table[slot]);
+            std::memcpy(ctx->table_key[slot], key, sizeof key);
+            ctx->table_valid[slot] = true;
+            ctx->table_stream[slot] = stream;
+        }
         table = ctx->d_table[slot];
     }
     for (int k = 0; k < 3; ++k) {

@@ -265,22 +265,24 @@ def test_many_calls_reuse_slots(l3, ctx):
 # ---------------------------------------------------------------------------
 # fused crop + flip + normalise (configs[4])
 
-def tensor_case(l3, ctx, images, crops, crop, dtype, patch=0):
+def tensor_case(l3, ctx, images, crops, crop, dtype, patch=0, mean=None, stdv=None):
+    mean = synth.IMAGENET_MEAN if mean is None else mean
+    stdv = synth.IMAGENET_STD if stdv is None else stdv
     files = [oracle.encode(im, patch) for im in images]
     infos = [l3.peek_header(f) for f in files]
     dfiles, keep = upload_files(files)
     n = len(files)
     out = torch.full((n, 3, crop, crop), -1, dtype=torch.int16, device="cuda")
     status = torch.zeros(n, dtype=torch.int32, device="cuda")
-    l3.decode_crop_normalize_batch(ctx, dfiles, infos, crops, crop, crop, synth.IMAGENET_MEAN,
-                                   synth.IMAGENET_STD, out, dtype=dtype, status=status)
+    l3.decode_crop_normalize_batch(ctx, dfiles, infos, crops, crop, crop, mean, stdv, out,
+                                   dtype=dtype, status=status)
     torch.cuda.synchronize()
     got = out.cpu().numpy().view(np.uint16)
     assert (status.cpu().numpy() == 0).all()
     ftype = torch.bfloat16 if dtype == 0 else torch.float16
     for i, (im, (x0, y0, flip)) in enumerate(zip(images, crops)):
-        want = oracle.crop_normalize(oracle.decode(files[i]), x0, y0, flip, crop, crop,
-                                     synth.IMAGENET_MEAN, synth.IMAGENET_STD, dtype)
+        want = oracle.crop_normalize(oracle.decode(files[i]), x0, y0, flip, crop, crop, mean, stdv,
+                                     dtype)
         a = torch.from_numpy(got[i].view(np.int16)).view(ftype).float()
         b = torch.from_numpy(want.view(np.int16)).view(ftype).float()
         assert float((a - b).abs().max()) <= 1e-3          # the stated tolerance
@@ -296,6 +298,19 @@ def test_fused_crop_normalize_config5(l3, ctx):
     crops = synth.config5_crops(shapes)
     tensor_case(l3, ctx, images, crops, 224, 0)
     tensor_case(l3, ctx, images[:6], crops[:6], 224, 1)
+
+
+def test_fused_constants_change_between_calls(l3, ctx):
+    """The normalisation table is kept between calls: ten calls on one context that
+    alternate between three sets of constants and the two output types must each use
+    their own."""
+    im = synth.cosine_field(83, 260, 240)
+    crops = [(3, 5, 0), (20, 10, 1)]
+    sets = [(synth.IMAGENET_MEAN, synth.IMAGENET_STD), ((0.5, 0.5, 0.5), (0.25, 0.5, 1.0)),
+            ((0.0, 0.1, 0.9), (1.0, 2.0, 0.125))]
+    for k in range(10):
+        mean, stdv = sets[k % 3]
+        tensor_case(l3, ctx, [im, im], crops, 224, k % 2, mean=mean, stdv=stdv)
 
 
 def test_fused_crop_edges(l3, ctx):
