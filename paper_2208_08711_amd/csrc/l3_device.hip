@@ -277,11 +277,18 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                     const u32x3 v = {o0, o1, o2};
                     __builtin_nontemporal_store(v, reinterpret_cast<global_u32x3_any*>(row + column));
                 } else if (nvalid) {
+                    /* the last word of an image row: 3, 6 or 9 bytes in two stores */
                     global_u8* b = row + column;
-#pragma unroll
-                    for (int k = 0; k < 9; ++k) {
-                        const uint32_t word = k < 4 ? o0 : (k < 8 ? o1 : o2);
-                        if ((uint32_t)k < 3 * nvalid) b[k] = (uint8_t)(word >> (8 * (k & 3)));
+                    if (nvalid == 3) {
+                        const u32x2 v = {o0, o1};
+                        *reinterpret_cast<global_u32x2_any*>(b) = v;
+                        b[8] = (uint8_t)o2;
+                    } else if (nvalid == 2) {
+                        *reinterpret_cast<global_u32_any*>(b) = o0;
+                        *reinterpret_cast<global_u16_any*>(b + 4) = (uint16_t)o1;
+                    } else {
+                        *reinterpret_cast<global_u16_any*>(b) = (uint16_t)o0;
+                        b[2] = (uint8_t)(o0 >> 16);
                     }
                 }
             } else if (MODE == L3_MODE_CHW) {

@@ -29,6 +29,8 @@ typedef __attribute__((address_space(1))) u32_any global_u32_any;
 typedef __attribute__((address_space(1))) u32x2_any global_u32x2_any;
 typedef __attribute__((address_space(1))) uint8_t global_u8;
 typedef __attribute__((address_space(1))) uint16_t global_u16;
+typedef uint16_t u16_any __attribute__((aligned(1)));
+typedef __attribute__((address_space(1))) u16_any global_u16_any;
 
 __device__ __forceinline__ uint32_t dpp_from_lower_lane(uint32_t v) {   /* lane i <- lane i-1, lane 0 <- 0 */
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
