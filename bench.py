@@ -508,18 +508,22 @@ def main():
         sample = files if args.workload != "imagenet" else files[:128]
         sample_bytes = sum(images[i].size for i in range(len(sample)))
         oracle.decode(sample[0])                               # warm-up
+        single = sample[:max(1, len(sample) // (4 if args.workload == "imagenet" else 1))]
         t = time.perf_counter()
-        for f in sample[:max(1, len(sample) // 4)]:
+        for f in single:
             oracle.decode(f)
-        one = (time.perf_counter() - t) / max(1, len(sample) // 4)
+        one = (time.perf_counter() - t) / len(single)
+        many = float("inf")
         with ThreadPoolExecutor(cores) as pool:
-            t = time.perf_counter()
-            list(pool.map(oracle.decode, sample))
-            many = time.perf_counter() - t
+            for _ in range(3):                                 # best of three passes
+                t = time.perf_counter()
+                list(pool.map(oracle.decode, sample))
+                many = min(many, time.perf_counter() - t)
         result["cpu_baseline"] = {
             "value": len(sample) / many, "unit": "images/s", "cores": cores, "kind": "oracle",
-            "sample": f"{len(sample)} images of the same batch, one pass over {cores} threads "
-                      f"(one image per task); single thread: {1.0 / one:.2f} images/s",
+            "sample": f"{len(sample)} images of the same batch, best of three passes over {cores} "
+                      f"threads (one image per task); single thread over {len(single)} images: "
+                      f"{1.0 / one:.2f} images/s",
             "decoded_GBps": sample_bytes / many / 1e9,
             "single_thread_images_per_s": 1.0 / one,
         }
