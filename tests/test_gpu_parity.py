@@ -332,3 +332,38 @@ def test_fused_crop_edges(l3, ctx):
     torch.cuda.synchronize()
     want = oracle.crop_normalize(small, 0, 0, 1, 50, 40, synth.IMAGENET_MEAN, synth.IMAGENET_STD, 0)
     assert np.array_equal(out.cpu().numpy().view(np.uint16)[0], want)
+
+
+def test_decode_batch_replayed_from_a_captured_graph(l3, ctx):
+    """Batches of at most 32 images carry their descriptors in the kernel arguments and
+    allocate nothing once the context is warm, so the call can be captured into a HIP
+    graph.  Every replay (with eager work and synchronisation between them) must give the
+    eager result."""
+    images = [synth.voronoi_scene(3300 + k, 300 + 7 * k, 150 + 3 * k, sites=9) for k in range(5)]
+    files = [oracle.encode(im) for im in images]
+    infos = [l3.peek_header(f) for f in files]
+    dfiles, keep = upload_files(files)
+    outs = [torch.zeros((im.shape[0], im.shape[1] * 3), dtype=torch.uint8, device="cuda") for im in images]
+    status = torch.full((len(files),), 9, dtype=torch.int32, device="cuda")
+    batch = l3.PreparedBatch(dfiles, infos, outs)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        l3.decode_batch_prepared(ctx, batch, status=status, stream=side)      # warm, eager
+    torch.cuda.synchronize()
+    want = [t.cpu().numpy().copy() for t in outs]
+    for w_, im in zip(want, images):
+        assert np.array_equal(w_.reshape(im.shape), im)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        l3.decode_batch_prepared(ctx, batch, status=status, stream=torch.cuda.current_stream())
+    for rep in range(4):
+        for t in outs:
+            t.fill_(rep + 1)                 # eager work between the replays
+        status.fill_(5)
+        torch.cuda.synchronize()
+        print(f"graph replay {rep}", flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (status.cpu().numpy() == 0).all()
+        for t, w_ in zip(outs, want):
+            assert np.array_equal(t.cpu().numpy(), w_)
