@@ -156,6 +156,24 @@ def test_config3_full_batch_bench_configuration(l3, ctx):
     check_batch(l3, ctx, synth.config3(32))
 
 
+def test_config2_full_batch_bench_configuration(l3, ctx):
+    """configs[1] at full size, as the benchmark launches it: 256 images of 400-500 x 300-375 in
+    one call (descriptor table pulled from pinned memory, N = 32), every byte compared."""
+    check_batch(l3, ctx, synth.config2(256))
+
+
+def test_config4_full_batch_bench_configuration(l3, ctx):
+    """configs[3] at full size: 8 images of 3840x2160, four compressible and four random."""
+    check_batch(l3, ctx, synth.config4(8))
+
+
+def test_config5_full_batch_bench_configuration(l3, ctx):
+    """configs[4] at full size: the 256-image batch through the fused window / mirror /
+    normalise path, bf16, every element compared."""
+    shapes = synth.config2_shapes(256)
+    tensor_case(l3, ctx, synth.config2(256), synth.config5_crops(shapes), 224, 0)
+
+
 @pytest.mark.parametrize("ppl", ["4", "8"])
 def test_both_lane_widths(l3, ctx, ppl, monkeypatch):
     """The kernel exists with 4 and with 8 pixels per lane; the library picks one per
