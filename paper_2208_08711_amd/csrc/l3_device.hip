@@ -317,35 +317,45 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
                 if (row >= 0 && row < (int32_t)crop_h && nvalid) {
                     const int32_t col0 = (int32_t)x - win_x0;   /* window column of pixel 0 */
                     const bool whole = nvalid == 4 && col0 >= 0 && col0 + 4 <= (int32_t)crop_w;
+                    /* all twelve table reads first, so that they travel together */
+                    uint32_t e[3][4];
 #pragma unroll
                     for (int ch = 0; ch < 3; ++ch) {
                         const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
-                        const uint32_t e0 = s_lut[ch * 256 + (word & 0xFFu)];
-                        const uint32_t e1 = s_lut[ch * 256 + ((word >> 8) & 0xFFu)];
-                        const uint32_t e2 = s_lut[ch * 256 + ((word >> 16) & 0xFFu)];
-                        const uint32_t e3 = s_lut[ch * 256 + (word >> 24)];
-                        uint8_t* base = reinterpret_cast<uint8_t*>((uintptr_t)(out_base + (((uint64_t)ch * crop_h + row) * crop_w) * 2));
-                        if (whole) {
+                        e[ch][0] = s_lut[ch * 256 + (word & 0xFFu)];
+                        e[ch][1] = s_lut[ch * 256 + ((word >> 8) & 0xFFu)];
+                        e[ch][2] = s_lut[ch * 256 + ((word >> 16) & 0xFFu)];
+                        e[ch][3] = s_lut[ch * 256 + (word >> 24)];
+                    }
+                    /* element (ch, row, 0) of this image; planes are crop_h * crop_w apart */
+                    global_u16* line = reinterpret_cast<global_u16*>((uintptr_t)out_base) + (size_t)row * crop_w;
+                    const size_t plane = (size_t)crop_h * crop_w;
+                    if (whole) {
+                        uint32_t col = (uint32_t)(win_flip ? (int32_t)crop_w - 4 - col0 : col0);
+                        asm volatile("" : "+v"(col));      /* stays the store's 32-bit offset */
+#pragma unroll
+                        for (int ch = 0; ch < 3; ++ch) {
                             u32x2 v;
-                            int32_t col;
                             if (win_flip) {
-                                col = (int32_t)crop_w - 4 - col0;
-                                v.x = e3 | (e2 << 16);
-                                v.y = e1 | (e0 << 16);
+                                v.x = e[ch][3] | (e[ch][2] << 16);
+                                v.y = e[ch][1] | (e[ch][0] << 16);
                             } else {
-                                col = col0;
-                                v.x = e0 | (e1 << 16);
-                                v.y = e2 | (e3 << 16);
+                                v.x = e[ch][0] | (e[ch][1] << 16);
+                                v.y = e[ch][2] | (e[ch][3] << 16);
                             }
-                            __builtin_nontemporal_store(v, reinterpret_cast<global_u32x2_any*>((uintptr_t)(base + (size_t)col * 2)));
-                        } else {
-                            global_u16* out16 = reinterpret_cast<global_u16*>((uintptr_t)base);
+                            __builtin_nontemporal_store(
+                                v, reinterpret_cast<global_u32x2_any*>(line + ch * plane + col));
+                        }
+                    } else {
+#pragma unroll
+                        for (int ch = 0; ch < 3; ++ch) {
+                            global_u16* out16 = line + ch * plane;
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
                                 int32_t col = col0 + k;
                                 if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
                                     if (win_flip) col = (int32_t)crop_w - 1 - col;
-                                    out16[col] = (uint16_t)(k == 0 ? e0 : (k == 1 ? e1 : (k == 2 ? e2 : e3)));
+                                    out16[col] = (uint16_t)e[ch][k];
                                 }
                             }
                         }
