@@ -184,10 +184,12 @@ def measure_ablation(torch, l3, ctx, images, files, infos, stream, patch, produc
                 for im in images]
         sets[custom] = (l3.PreparedBatch(dfiles, finfos, outs), outs, sum(map(len, fl)))
     PB, CF, SP = l3.ABLATION_PIXEL_BD, l3.ABLATION_CUSTOM_FILTER, l3.ABLATION_SERIAL_PATCHES
+    DG = l3.ABLATION_DIAGONAL
     variants = [("baseline: original filter, one lane per patch for both stages", 0),
                 ("+pixel-wise base-delta", PB),
                 ("+custom filter", CF),
                 ("+pixel-wise base-delta +custom filter", PB | CF),
+                ("+pixel-wise base-delta, original filter along anti-diagonals (not in the paper)", PB | DG),
                 ("baseline, patches of an image in turn", SP),
                 ("+both, patches of an image in turn", PB | CF | SP)]
     rows = []

@@ -35,14 +35,18 @@ l3_status l3_ablation_encode_cpu(const uint8_t* rgb_hwc, uint32_t width, uint32_
 enum {
     L3_ABLATION_PIXEL_BD = 1,        /* one lane per pixel of a row extracts its delta */
     L3_ABLATION_CUSTOM_FILTER = 2,   /* files use the custom filter; undone row-parallel */
-    L3_ABLATION_SERIAL_PATCHES = 4   /* one workgroup per image takes its patches in turn */
+    L3_ABLATION_SERIAL_PATCHES = 4,  /* one workgroup per image takes its patches in turn */
+    L3_ABLATION_DIAGONAL = 8         /* original filter undone one anti-diagonal per step (not in
+                                        the paper: the best schedule its dependencies allow);
+                                        not together with L3_ABLATION_CUSTOM_FILTER */
 };
 
 /* Decodes n files (l3_item as for l3_decode_batch; interleaved RGB output) with the
  * variant that `variant` (a combination of the flags above) selects.  Without
  * L3_ABLATION_PIXEL_BD a single lane decodes the base-delta stream of a patch;
  * without L3_ABLATION_CUSTOM_FILTER the files must have been written with the
- * original filter and a single lane undoes it in raster order.  One wave works on one
+ * original filter and a single lane undoes it in raster order (or, with
+ * L3_ABLATION_DIAGONAL, all lanes undo it along anti-diagonals).  One wave works on one
  * patch of one channel, from a copy of the patch stream in local memory.
  * Any patch size 1..128.  A damaged stream yields unspecified pixels inside the
  * image's own output rectangle; nothing is read outside the file or written outside

@@ -8,5 +8,5 @@ from .binding import (  # noqa: F401
     decode_batch, decode_crop_normalize_batch, PreparedBatch, decode_batch_prepared,
     PreparedCropBatch, decode_crop_normalize_batch_prepared, encode_batch, library_path, status_string,
     LAYOUT_HWC, LAYOUT_CHW, BF16, FP16, EXPORTED_SYMBOLS,
-    ablation_decode_batch, ABLATION_PIXEL_BD, ABLATION_CUSTOM_FILTER, ABLATION_SERIAL_PATCHES,
+    ablation_decode_batch, ABLATION_PIXEL_BD, ABLATION_CUSTOM_FILTER, ABLATION_SERIAL_PATCHES, ABLATION_DIAGONAL,
 )

@@ -217,7 +217,7 @@ def decode_batch(ctx, files, infos, outs, layout=LAYOUT_HWC, status=None, stream
                                    _stream_ptr(stream)), "l3_decode_batch")
 
 
-ABLATION_PIXEL_BD, ABLATION_CUSTOM_FILTER, ABLATION_SERIAL_PATCHES = 1, 2, 4
+ABLATION_PIXEL_BD, ABLATION_CUSTOM_FILTER, ABLATION_SERIAL_PATCHES, ABLATION_DIAGONAL = 1, 2, 4, 8
 
 
 def ablation_decode_batch(ctx, batch, variant, stream=None):

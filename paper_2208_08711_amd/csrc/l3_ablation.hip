@@ -65,7 +65,7 @@ __device__ __forceinline__ int select_original(int left, int top, int corner) {
 
 template <bool PIXEL_BD, bool CUSTOM>
 __global__ __launch_bounds__(kLanes) void l3_ablation_kernel(const AblationDesc* __restrict__ descs,
-                                                             int serial_patches) {
+                                                             int serial_patches, int diagonal) {
     __shared__ uint32_t s_stream[kStreamWords];
     __shared__ uint8_t s_pix[kMaxN * kMaxN];
 
@@ -142,6 +142,22 @@ __global__ __launch_bounds__(kLanes) void l3_ablation_kernel(const AblationDesc*
                 }
                 __syncthreads();
             }
+        } else if (diagonal) {
+            /* the original filter's dependencies (left, top, top-left) all point to the two
+             * previous anti-diagonals x + y = d - 1, d - 2: one diagonal per step, its pixels
+             * in parallel */
+            for (uint32_t d = 1; d + 1 < pw + ph; ++d) {
+                for (uint32_t x = lane; x < pw; x += kLanes) {
+                    const uint32_t y = d - x;              /* wraps to a huge value when x > d */
+                    if (y >= 1 && y < ph) {
+                        uint8_t* cur = &s_pix[y * n];
+                        const uint8_t* up = cur - n;
+                        const int pred = x == 0 ? up[0] : select_original(cur[x - 1], up[x], up[x - 1]);
+                        cur[x] = (uint8_t)(cur[x] + pred);
+                    }
+                }
+                __syncthreads();
+            }
         } else if (lane == 0) {
             for (uint32_t r = 1; r < ph; ++r) {
                 const uint8_t* up = &s_pix[(r - 1) * n];
@@ -178,7 +194,9 @@ void l3_ablation_state_free(L3AblationState* s) {
 
 extern "C" l3_status l3_ablation_decode_batch(l3_ctx* ctx, const l3_item* items, int n, int variant,
                                               void* stream_v) {
-    if (!ctx || n < 0 || (n > 0 && !items) || (variant & ~7)) return L3_ERR_INVALID_ARG;
+    if (!ctx || n < 0 || (n > 0 && !items) || (variant & ~15)) return L3_ERR_INVALID_ARG;
+    if ((variant & L3_ABLATION_DIAGONAL) && (variant & L3_ABLATION_CUSTOM_FILTER))
+        return L3_ERR_INVALID_ARG;
     if (n == 0) return L3_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return L3_ERR_DEVICE;
@@ -243,15 +261,16 @@ extern "C" l3_status l3_ablation_decode_batch(l3_ctx* ctx, const l3_item* items,
     }
 
     const int serial = (variant & L3_ABLATION_SERIAL_PATCHES) ? 1 : 0;
+    const int diagonal = (variant & L3_ABLATION_DIAGONAL) ? 1 : 0;
     const dim3 grid(serial ? 1u : max_units, (uint32_t)n), block(kLanes);
     const bool pixel_bd = variant & L3_ABLATION_PIXEL_BD, custom = variant & L3_ABLATION_CUSTOM_FILTER;
     if (pixel_bd && custom)
-        hipLaunchKernelGGL((l3_ablation_kernel<true, true>), grid, block, 0, stream, st->d_descs, serial);
+        hipLaunchKernelGGL((l3_ablation_kernel<true, true>), grid, block, 0, stream, st->d_descs, serial, diagonal);
     else if (pixel_bd)
-        hipLaunchKernelGGL((l3_ablation_kernel<true, false>), grid, block, 0, stream, st->d_descs, serial);
+        hipLaunchKernelGGL((l3_ablation_kernel<true, false>), grid, block, 0, stream, st->d_descs, serial, diagonal);
     else if (custom)
-        hipLaunchKernelGGL((l3_ablation_kernel<false, true>), grid, block, 0, stream, st->d_descs, serial);
+        hipLaunchKernelGGL((l3_ablation_kernel<false, true>), grid, block, 0, stream, st->d_descs, serial, diagonal);
     else
-        hipLaunchKernelGGL((l3_ablation_kernel<false, false>), grid, block, 0, stream, st->d_descs, serial);
+        hipLaunchKernelGGL((l3_ablation_kernel<false, false>), grid, block, 0, stream, st->d_descs, serial, diagonal);
     return hipGetLastError() == hipSuccess ? L3_OK : L3_ERR_DEVICE;
 }

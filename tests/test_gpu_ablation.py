@@ -48,7 +48,7 @@ def _run(l3, ctx, files, variant, pad=5, poison=0xA7):
     return res
 
 
-@pytest.mark.parametrize("variant", range(8))
+@pytest.mark.parametrize("variant", list(range(8)) + [8, 9, 12, 13])
 @pytest.mark.parametrize("patch", [7, 32, 64, 128])
 def test_ablation_variant_matches_oracle(l3, ctx, variant, patch):
     custom = bool(variant & l3.ABLATION_CUSTOM_FILTER)
@@ -80,9 +80,10 @@ def test_ablation_rejects_bad_arguments(l3, ctx):
     info = l3.peek_header(f)
     d = torch.from_numpy(np.frombuffer(f, dtype=np.uint8).copy()).cuda()
     out = torch.zeros((30, 120), dtype=torch.uint8, device="cuda")
-    with pytest.raises(l3.L3Error) as e:
-        l3.ablation_decode_batch(ctx, l3.PreparedBatch([d], [info], [out]), 8)
-    assert e.value.code == 1
+    for bad in (16, l3.ABLATION_DIAGONAL | l3.ABLATION_CUSTOM_FILTER):
+        with pytest.raises(l3.L3Error) as e:
+            l3.ablation_decode_batch(ctx, l3.PreparedBatch([d], [info], [out]), bad)
+        assert e.value.code == 1
     with pytest.raises(l3.L3Error) as e:
         l3.ablation_decode_batch(ctx, l3.PreparedBatch([d], [info], [out], row_strides=[100]), 3)
     assert e.value.code == 1
