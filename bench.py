@@ -57,6 +57,10 @@ def make_workload(name, batch=0):
         n = batch or 32
         return synth.config3(n), ("Cityscapes-shaped: %d RGB images 2048x1024, Voronoi regions + texture, "
                                   "N=128" % n)
+    if name == "fhd":
+        n = batch or 32
+        return synth.config3(n, width=1920, height=1080), ("FHD: %d RGB images 1920x1080, Voronoi regions + "
+                                                           "texture, N=64" % n)
     if name == "imagenet":
         return synth.config2(256), "ImageNet-shaped: 256 RGB images 400-500 x 300-375, cosine field + noise, N=32"
     if name == "train224":
@@ -307,7 +311,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="cityscapes")
+    ap.add_argument("--workload", default="cityscapes",
+                    help="cityscapes (default, the configuration the metric is quoted on), fhd, imagenet, "
+                         "uhd, train224")
     ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
