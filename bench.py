@@ -309,8 +309,8 @@ def measure_overlap(torch, step, stream, steps, decode_alone_ms):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=3000)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="cityscapes",
                     help="cityscapes (default, the configuration the metric is quoted on), fhd, imagenet, "
                          "uhd, train224")
