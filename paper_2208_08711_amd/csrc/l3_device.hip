@@ -34,6 +34,7 @@
  */
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -112,9 +113,9 @@ __device__ __forceinline__ uint32_t load_u32_any_alignment(const uint8_t* p) {
 /* ---- the decode kernel ---------------------------------------------------- */
 
 template <int N, int PPL, int MODE>
-__device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __restrict__ status,
-                                            uint32_t crop_w, uint32_t crop_h,
-                                            const uint16_t* __restrict__ lut) {
+__device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t unit,
+                                            uint32_t* __restrict__ status, uint32_t crop_w,
+                                            uint32_t crop_h, const uint16_t* __restrict__ lut) {
     using G = Geom<N, PPL>;
     constexpr int LPT = G::LPT, TPW = G::TPW, GPL = G::GPL, NW = G::NW, NP = G::NP, QW = G::QW;
     constexpr int CHUNK = G::CHUNK, RING = G::RING, P = G::P;
@@ -130,7 +131,6 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t c = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   /* this wave's channel */
-    const uint32_t unit = blockIdx.x;
     if (unit >= d.units) return;                                           /* whole workgroup */
 
     const uint32_t g = lane / LPT, xl = lane % LPT;
@@ -503,12 +503,29 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, uint32_t* __re
     if (flags && active && status) atomicOr(&status[d.status_index], flags);
 }
 
+/* Which (image, unit) a workgroup takes.  The grid is one-dimensional, a multiple of 8
+ * long, and the hardware hands consecutive workgroups to the 8 XCDs in turn (workgroup L
+ * runs on XCD L mod 8).  Work item number (L mod 8) * grid/8 + L / 8 therefore gives every
+ * XCD one contiguous eighth of the (image, unit) sequence: neighbouring strips, whose
+ * streams and output rows share cache lines, meet in the same L2. */
+__device__ __forceinline__ bool take_work(uint32_t units_per_image, uint32_t images, uint32_t& image,
+                                          uint32_t& unit) {
+    const uint32_t eighth = gridDim.x >> 3;
+    const uint32_t item = (blockIdx.x & 7u) * eighth + (blockIdx.x >> 3);
+    image = item / units_per_image;
+    unit = item - image * units_per_image;
+    return image < images;
+}
+
 /* Descriptors in a device table (any batch size)... */
 template <int N, int PPL, int MODE>
 __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel(
-    const L3ImageDesc* __restrict__ descs, uint32_t* __restrict__ status, uint32_t crop_w,
-    uint32_t crop_h, const uint16_t* __restrict__ lut) {
-    decode_unit<N, PPL, MODE>(descs[blockIdx.y], status, crop_w, crop_h, lut);
+    const L3ImageDesc* __restrict__ descs, uint32_t units_per_image, uint32_t images,
+    uint32_t* __restrict__ status, uint32_t crop_w, uint32_t crop_h,
+    const uint16_t* __restrict__ lut) {
+    uint32_t image, unit;
+    if (!take_work(units_per_image, images, image, unit)) return;
+    decode_unit<N, PPL, MODE>(descs[image], unit, status, crop_w, crop_h, lut);
 }
 
 /* ...or, for small batches, inside the kernel arguments: no upload, no dependency
@@ -519,9 +536,11 @@ static_assert(sizeof(DescPack) + 64 <= 4096, "kernel argument segment");
 
 template <int N, int PPL, int MODE>
 __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel_args(
-    const DescPack pack, uint32_t* __restrict__ status, uint32_t crop_w, uint32_t crop_h,
-    const uint16_t* __restrict__ lut) {
-    decode_unit<N, PPL, MODE>(pack.d[blockIdx.y], status, crop_w, crop_h, lut);
+    const DescPack pack, uint32_t units_per_image, uint32_t images, uint32_t* __restrict__ status,
+    uint32_t crop_w, uint32_t crop_h, const uint16_t* __restrict__ lut) {
+    uint32_t image, unit;
+    if (!take_work(units_per_image, images, image, unit)) return;
+    decode_unit<N, PPL, MODE>(pack.d[image], unit, status, crop_w, crop_h, lut);
 }
 
 /* y = (x/255 - mean) / stdv for all 256 byte values of each channel, IEEE
@@ -568,8 +587,10 @@ __global__ void l3_prepare_kernel(const uint64_t* __restrict__ pinned_src, uint6
 /* ---- host side: context, planning, launch ------------------------------- */
 
 
-typedef void (*decode_kernel_t)(const L3ImageDesc*, uint32_t*, uint32_t, uint32_t, const uint16_t*);
-typedef void (*decode_kernel_args_t)(const DescPack, uint32_t*, uint32_t, uint32_t, const uint16_t*);
+typedef void (*decode_kernel_t)(const L3ImageDesc*, uint32_t, uint32_t, uint32_t*, uint32_t, uint32_t,
+                                const uint16_t*);
+typedef void (*decode_kernel_args_t)(const DescPack, uint32_t, uint32_t, uint32_t*, uint32_t, uint32_t,
+                                     const uint16_t*);
 
 struct KernelChoice {
     decode_kernel_t table;        /* descriptors in a device table */
@@ -806,18 +827,24 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         const int count = class_begin[k + 1] - class_begin[k];
         if (count == 0 || max_units[k] == 0) continue;
         const uint32_t gx = max_units[k];
+        /* one-dimensional grid, rounded up to a multiple of 8 (see take_work) */
+        const auto grid_for = [gx](uint64_t images) { return (uint32_t)((gx * images + 7) / 8 * 8); };
         if (in_args) {
             DescPack pack;
             std::memcpy(pack.d, stage + class_begin[k], (size_t)count * sizeof(L3ImageDesc));
-            hipLaunchKernelGGL(pick_kernel(kClasses[k], mode).args, dim3(gx, (uint32_t)count),
-                               dim3(kBlockThreads), 0, stream, pack, d_status, crop_w, crop_h, table);
+            hipLaunchKernelGGL(pick_kernel(kClasses[k], mode).args, dim3(grid_for((uint64_t)count)),
+                               dim3(kBlockThreads), 0, stream, pack, gx, (uint32_t)count, d_status, crop_w,
+                               crop_h, table);
             continue;
         }
         decode_kernel_t kern = pick_kernel(kClasses[k], mode).table;
-        for (int first = 0; first < count; first += 65535) {
-            const int m = count - first < 65535 ? count - first : 65535;
-            hipLaunchKernelGGL(kern, dim3(gx, (uint32_t)m), dim3(kBlockThreads), 0, stream,
-                               d_descs + class_begin[k] + first, d_status, crop_w, crop_h, table);
+        if (gx > 0x7FFFFF00u) return L3_ERR_UNSUPPORTED;     /* more units in one image than a grid holds */
+        const int per_launch = (int)std::min<uint64_t>((uint64_t)count, 0x7FFFFF00ull / gx);
+        for (int first = 0; first < count; first += per_launch) {
+            const int m = count - first < per_launch ? count - first : per_launch;
+            hipLaunchKernelGGL(kern, dim3(grid_for((uint64_t)m)), dim3(kBlockThreads), 0, stream,
+                               d_descs + class_begin[k] + first, gx, (uint32_t)m, d_status, crop_w, crop_h,
+                               table);
         }
     }
     if (hipGetLastError() != hipSuccess) return L3_ERR_DEVICE;
