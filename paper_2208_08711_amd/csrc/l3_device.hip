@@ -503,20 +503,6 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     if (flags && active && status) atomicOr(&status[d.status_index], flags);
 }
 
-/* Which (image, unit) a workgroup takes.  The grid is one-dimensional, a multiple of 8
- * long, and the hardware hands consecutive workgroups to the 8 XCDs in turn (workgroup L
- * runs on XCD L mod 8).  Work item number (L mod 8) * grid/8 + L / 8 therefore gives every
- * XCD one contiguous eighth of the (image, unit) sequence: neighbouring strips, whose
- * streams and output rows share cache lines, meet in the same L2. */
-__device__ __forceinline__ bool take_work(uint32_t units_per_image, uint32_t images, uint32_t& image,
-                                          uint32_t& unit) {
-    const uint32_t eighth = gridDim.x >> 3;
-    const uint32_t item = (blockIdx.x & 7u) * eighth + (blockIdx.x >> 3);
-    image = item / units_per_image;
-    unit = item - image * units_per_image;
-    return image < images;
-}
-
 /* Descriptors in a device table (any batch size)... */
 template <int N, int PPL, int MODE>
 __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel(
