@@ -174,6 +174,34 @@ def test_config5_full_batch_bench_configuration(l3, ctx):
     tensor_case(l3, ctx, synth.config2(256), synth.config5_crops(shapes), 224, 0)
 
 
+@pytest.mark.parametrize("layout", ["hwc", "chw"])
+def test_seeded_random_shapes_one_call(l3, ctx, layout):
+    """120 images of seeded random size (1..400 x 1..260), content kind and patch size
+    (32 / 64 / 128, forty of each: above the 32 per class that fit the kernel arguments, so the
+    descriptor-table route with three launches) in one call, padded output rows."""
+    gen = synth.Stream(0xC0FFEE, 7)
+    images, patches = [], []
+    for k in range(120):
+        w = int(gen.integers(1, 400)[0])
+        h = int(gen.integers(1, 260)[0])
+        kind = int(gen.integers(0, 3)[0])
+        if kind == 0:
+            im = synth.gradient_noise(5000 + k, w, h, 3.0)
+        elif kind == 1:
+            im = synth.cosine_field(5000 + k, w, h)
+        elif kind == 2:
+            im = synth.voronoi_scene(5000 + k, w, h, sites=6)
+        else:
+            im = synth.uniform_bytes(5000 + k, w, h)
+        images.append(im)
+        patches.append((32, 64, 128)[k % 3])
+    files = [oracle.encode(im, p) for im, p in zip(images, patches)]
+    got, status = gpu_decode(l3, ctx, files, layout, pad_cols=3)
+    assert (status == 0).all(), status
+    for k, (g, im) in enumerate(zip(got, images)):
+        assert np.array_equal(g, im), (k, im.shape, patches[k])
+
+
 @pytest.mark.parametrize("ppl", ["4", "8"])
 def test_both_lane_widths(l3, ctx, ppl, monkeypatch):
     """The kernel exists with 4 and with 8 pixels per lane; the library picks one per
