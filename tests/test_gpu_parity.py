@@ -413,3 +413,59 @@ def test_decode_batch_replayed_from_a_captured_graph(l3, ctx):
         assert (status.cpu().numpy() == 0).all()
         for t, w_ in zip(outs, want):
             assert np.array_equal(t.cpu().numpy(), w_)
+
+
+def _decode_many_small(l3, ctx, images):
+    """Thousands of tiny images in one call: one output buffer, one slot of 64 bytes each."""
+    files = [oracle.encode(im, 32) for im in images]
+    infos = [l3.peek_header(f) for f in files]
+    dfiles, keep = upload_files(files, misalign=False)
+    n = len(files)
+    out = torch.full((n, 64), 0x5A, dtype=torch.uint8, device="cuda")
+    outs = [out[i] for i in range(n)]
+    status = torch.full((n,), 3, dtype=torch.int32, device="cuda")
+    l3.decode_batch(ctx, dfiles, infos, outs, status=status)
+    torch.cuda.synchronize()
+    assert int(status.abs().sum()) == 0
+    return out.cpu().numpy()
+
+
+def test_every_pair_of_values_in_a_column(l3, ctx):
+    """All 65,536 (top, bottom) byte pairs as 1 x 2 images (three different pairings in the
+    three channels): the modulo-256 arithmetic of base, delta and predictor for every value."""
+    a, b = np.meshgrid(np.arange(256, dtype=np.uint8), np.arange(256, dtype=np.uint8), indexing="ij")
+    a, b = a.ravel(), b.ravel()
+    images = []
+    for i in range(a.size):
+        im = np.empty((2, 1, 3), np.uint8)
+        im[0, 0] = (a[i], b[i], 255 - a[i])
+        im[1, 0] = (b[i], a[i], b[i])
+        images.append(im)
+    got = _decode_many_small(l3, ctx, images)
+    want = np.stack([im.reshape(-1) for im in images])
+    assert np.array_equal(got[:, :6], want)
+    assert (got[:, 6:] == 0x5A).all()
+
+
+def test_predictor_grid_on_the_gpu(l3, ctx):
+    """3 x 2 images: the upper row over the value grid {0, 1, 127, 128, 129, 200, 254, 255}^3,
+    the pixel below its centre over all 256 values (131,072 images): every kind of neighbour
+    ordering, tie and wrap goes through the packed predictor."""
+    grid = np.array([0, 1, 127, 128, 129, 200, 254, 255], dtype=np.uint8)
+    images = []
+    for tl in grid:
+        for t in grid:
+            for tr in grid:
+                for v in range(256):
+                    im = np.empty((2, 3, 3), np.uint8)
+                    im[0, :, 0] = (tl, t, tr)
+                    im[0, :, 1] = (tr, tl, t)
+                    im[0, :, 2] = (t, tr, tl)
+                    im[1, :, 0] = (tl, v, tr)
+                    im[1, :, 1] = (v, 255 - v, v)
+                    im[1, :, 2] = (tr, (v + 128) & 255, t)
+                    images.append(im)
+    got = _decode_many_small(l3, ctx, images)
+    want = np.stack([im.reshape(-1) for im in images])
+    assert np.array_equal(got[:, :18], want)
+    assert (got[:, 18:] == 0x5A).all()
