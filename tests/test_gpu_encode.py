@@ -191,3 +191,65 @@ def test_host_errors(l3, ctx):
     with pytest.raises(l3.L3Error) as e:
         l3.encode_batch(ctx, [_Shape(d, 200, 300)], [buf], lens, patch=32, row_strides=[899])
     assert e.value.code == 1
+
+
+def _encode_many_small(l3, ctx, images, patch):
+    """Thousands of tiny images of one shape in one call: one input and one output buffer."""
+    n = len(images)
+    h, w = images[0].shape[:2]
+    host = np.stack([im.reshape(h, 3 * w) for im in images])
+    dev = torch.from_numpy(host).cuda()
+    cap = l3.encode_bound(w, h, patch)
+    out = torch.full((n, cap + 8), 0xAB, dtype=torch.uint8, device="cuda")
+    lens = torch.zeros(n, dtype=torch.int64, device="cuda")
+    status = torch.full((n,), 7, dtype=torch.int32, device="cuda")
+    l3.encode_batch(ctx, [_Shape(dev[i], h, w) for i in range(n)], [out[i, :cap] for i in range(n)],
+                    lens, patch=patch, status=status)
+    torch.cuda.synchronize()
+    assert int(status.abs().sum()) == 0
+    return out.cpu().numpy(), lens.cpu().numpy()
+
+
+@pytest.mark.parametrize("patch", [32, 5])
+def test_every_pair_of_values_in_a_column_encodes_like_the_oracle(l3, ctx, patch):
+    """All 65,536 (top, bottom) byte pairs as 1 x 2 images, through the strip route (32) and the
+    plain route (5): signed / unsigned row views, widths 0..8 and wrap for every value."""
+    a, b = np.meshgrid(np.arange(256, dtype=np.uint8), np.arange(256, dtype=np.uint8), indexing="ij")
+    a, b = a.ravel(), b.ravel()
+    images = []
+    for i in range(a.size):
+        im = np.empty((2, 1, 3), np.uint8)
+        im[0, 0] = (a[i], b[i], 255 - a[i])
+        im[1, 0] = (b[i], a[i], b[i])
+        images.append(im)
+    got, lens = _encode_many_small(l3, ctx, images, patch)
+    for i in range(0, len(images)):
+        want = oracle.encode(images[i], patch)
+        assert lens[i] == len(want), i
+        assert got[i, :len(want)].tobytes() == want, i
+        assert (got[i, len(want):] == 0xAB).all(), i
+
+
+def test_three_pixel_rows_over_a_value_grid_encode_like_the_oracle(l3, ctx):
+    """3 x 2 images, upper row over {0, 1, 127, 128, 129, 200, 254, 255}^3, the pixel below its
+    centre over every 8th value plus the extremes: predictor choice, row minimum and width."""
+    grid = np.array([0, 1, 127, 128, 129, 200, 254, 255], dtype=np.uint8)
+    centre = sorted(set(range(0, 256, 8)) | {1, 127, 128, 129, 254, 255})
+    images = []
+    for tl in grid:
+        for t in grid:
+            for tr in grid:
+                for v in centre:
+                    im = np.empty((2, 3, 3), np.uint8)
+                    im[0, :, 0] = (tl, t, tr)
+                    im[0, :, 1] = (tr, tl, t)
+                    im[0, :, 2] = (t, tr, tl)
+                    im[1, :, 0] = (tl, v, tr)
+                    im[1, :, 1] = (v, 255 - v, v)
+                    im[1, :, 2] = (tr, (v + 128) & 255, t)
+                    images.append(im)
+    got, lens = _encode_many_small(l3, ctx, images, 32)
+    for i, im in enumerate(images):
+        want = oracle.encode(im, 32)
+        assert lens[i] == len(want), i
+        assert got[i, :len(want)].tobytes() == want, i
