@@ -121,7 +121,13 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     constexpr int CHUNK = G::CHUNK, RING = G::RING, P = G::P;
 
     __shared__ __attribute__((aligned(16))) uint32_t rings[3][TPW][G::RING_WORDS];
-    __shared__ __attribute__((aligned(8))) uint32_t parked[2][P][3][QW]; /* [buffer][row of period][channel][word] */
+    /* Where the period's barrier sits (see the period loop): behind row 0 for the
+     * small-patch pixel modes, where it measured 3 % faster; in front of row 0 otherwise
+     * (no gain at N = 128, and the third parking buffer it needs costs the fused path a
+     * workgroup per CU). */
+    constexpr bool LATE_BARRIER = N == 32 && MODE != L3_MODE_TENSOR;
+    constexpr int PARKS = LATE_BARRIER ? 3 : 2;
+    __shared__ __attribute__((aligned(8))) uint32_t parked[PARKS][P][3][QW]; /* [buffer][row of period][channel][word] */
     __shared__ uint16_t s_lut[MODE == L3_MODE_TENSOR ? 768 : 2];
 
     if (MODE == L3_MODE_TENSOR) {
@@ -443,9 +449,15 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     __builtin_amdgcn_s_setprio(3);
 
     /* Periods of P = 3 rows, unrolled so that the row's place in the period is a
-     * constant: the previous period is written out before row 0, the ring is topped
-     * up before row 2.  Only the last period can be shorter. */
-    uint32_t buf = 0;
+     * constant: the workgroup barrier and the write-out of the previous period, rows 0
+     * and 1, the ring top-up, row 2.  Only the last period can be shorter.
+     * With LATE_BARRIER the barrier and the write-out come behind row 0, so that a wave
+     * that arrives early has a row to do before it waits.  Three parking buffers in turn
+     * make that safe: a wave that parks period k has passed the barrier of period k-1,
+     * which every wave reaches only after it has written out period k-3, the previous
+     * tenant of the buffer.  (With two buffers a wave could still be writing out period
+     * k-2 when an early one starts to park period k.) */
+    uint32_t buf = 0, prev_buf = 0;
     for (uint32_t r = 0; r < ph; r += P) {
         const uint32_t rows = min((uint32_t)P, ph - r);
         if (r >= next_drop) {
@@ -455,10 +467,10 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
             else if (stage == 2) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
         }
-        if (r > 0) {
+        if (!LATE_BARRIER && r > 0) {
             /* all three channels of the previous period are parked: write them out */
             __syncthreads();
-            flush(buf ^ 1u, r - P, P);
+            flush(prev_buf, r - P, P);
         }
         /* interleaved mode: this lane's 12 NW bytes of the row, channel c first at byte c;
          * planar modes: this lane's NW words of channel c */
@@ -467,6 +479,10 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                                                            lane * (12 * NW) + c)
                              : &parked[buf][0][c][lane * NW];
         do_row(park);
+        if (LATE_BARRIER && r > 0) {
+            __syncthreads();
+            flush(prev_buf, r - P, P);
+        }
         if (rows > 1) do_row(park + 3 * QW);
         if (rows > 2) {
             if (r + P < ph) {
@@ -489,12 +505,13 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
             }
             do_row(park + 2 * 3 * QW);
         }
-        buf ^= 1u;
+        prev_buf = buf;
+        buf = buf == PARKS - 1 ? 0u : buf + 1u;
     }
     {
         const uint32_t first = ((ph - 1) / P) * P;
         __syncthreads();
-        flush(buf ^ 1u, first, ph - first);
+        flush(prev_buf, first, ph - first);
     }
 
     if (wmax > 8) flags |= L3_STATUS_BAD_WIDTH;
