@@ -31,6 +31,8 @@
  *     the group redundantly (broadcast reads), one row ahead of the arithmetic.
  *   - The upper-row neighbours come from registers: in-lane for the inner pixels,
  *     DPP wave shifts for the two pixels at the lane's edges.
+ *   - The grid is one-dimensional; every XCD takes a contiguous eighth of the
+ *     (image, strip) sequence, so that strips which share cache lines share an L2.
  */
 #include <hip/hip_runtime.h>
 
