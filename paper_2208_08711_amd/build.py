@@ -31,6 +31,23 @@ def build(verbose: bool = False) -> str:
     return OUT
 
 
+def build_c_example(verbose: bool = False) -> str:
+    """tests/native/abi_roundtrip.c -> abi_roundtrip.bin: the ABI used from plain C (gcc, C99),
+    linked against libl3.so and the HIP runtime.  A GPU test runs it."""
+    src = os.path.join(ROOT, "tests", "native", "abi_roundtrip.c")
+    out = os.path.join(ROOT, "tests", "native", "abi_roundtrip.bin")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-Wall", "-O1", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(rocm, "include"), src, "-o", out,
+           "-L", HERE, "-l:libl3.so", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2208_08711_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return out
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_c_example(verbose=True))
     sys.exit(0)

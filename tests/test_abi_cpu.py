@@ -128,3 +128,16 @@ def test_context_needs_a_gpu_and_says_so():
     with pytest.raises(l3.L3Error) as e:
         l3.Context(0)
     assert e.value.code == 7
+
+
+def test_header_is_plain_c99(tmp_path):
+    """include/l3.h and include/l3_ablation.h compile as C99 with every warning on (no GPU, no
+    HIP header needed): the ABI has no C++ in it."""
+    import subprocess
+    src = tmp_path / "use_headers.c"
+    src.write_text('#include "l3.h"\n#include "l3_ablation.h"\n'
+                   'int use(void) { l3_info i; l3_item it; l3_crop c; l3_encode_item e;\n'
+                   '  (void)i; (void)it; (void)c; (void)e; return (int)L3_ERR_DEVICE + (int)L3_LAYOUT_CHW + '
+                   '(int)L3_FP16 + L3_ABLATION_DIAGONAL; }\n')
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
+                    "-I", os.path.join(ROOT, "include"), str(src)], check=True)

@@ -469,3 +469,16 @@ def test_predictor_grid_on_the_gpu(l3, ctx):
     want = np.stack([im.reshape(-1) for im in images])
     assert np.array_equal(got[:, :18], want)
     assert (got[:, 18:] == 0x5A).all()
+
+
+def test_abi_from_plain_c():
+    """tests/native/abi_roundtrip.c (built with gcc as C99 next to the library): encode on the
+    host, decode on the GPU through the C ABI with nothing but the HIP runtime beside it."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "native", "abi_roundtrip.bin")
+    assert os.path.exists(exe), "build first: python -c 'import __graft_entry__ as g; g.build()'"
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    print(run.stdout, run.stderr, flush=True)
+    assert run.returncode == 0, (run.returncode, run.stderr)
+    assert "abi_roundtrip ok" in run.stdout
