@@ -329,6 +329,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, metavar="N",
                     help="cityscapes workload only: number of images per batch (default 32, the "
                          "configuration the metric is quoted on)")
+    ap.add_argument("--layout", default="hwc", choices=("hwc", "chw"),
+                    help="output layout of the plain decode (the headline is hwc)")
     ap.add_argument("--no-settle", action="store_true",
                     help="skip the extra untimed warm-up that waits for the clocks to settle")
     ap.add_argument("--ablation", action="store_true",
@@ -386,9 +388,14 @@ def main():
     else:
         for s in range(args.sets):
             dfiles = [torch.from_numpy(np.frombuffer(f, dtype=np.uint8).copy()).cuda() for f in files]
-            outs = [torch.empty((im.shape[0], im.shape[1] * 3), dtype=torch.uint8, device="cuda")
-                    for im in images]
-            sets.append((l3.PreparedBatch(dfiles, infos, outs), outs))
+            if args.layout == "chw":
+                outs = [torch.empty((3, im.shape[0], im.shape[1]), dtype=torch.uint8, device="cuda")
+                        for im in images]
+                sets.append((l3.PreparedBatch(dfiles, infos, outs, layout=l3.LAYOUT_CHW), outs))
+            else:
+                outs = [torch.empty((im.shape[0], im.shape[1] * 3), dtype=torch.uint8, device="cuda")
+                        for im in images]
+                sets.append((l3.PreparedBatch(dfiles, infos, outs), outs))
 
         def step(k):
             l3.decode_batch_prepared(ctx, sets[k % args.sets][0], stream=stream)
@@ -459,7 +466,9 @@ def main():
     else:
         for s in range(args.sets):
             for t, im in zip(sets[s][1], images):
-                if not np.array_equal(t.cpu().numpy().reshape(im.shape), im):
+                got = t.cpu().numpy()
+                got = got.transpose(1, 2, 0) if args.layout == "chw" else got.reshape(im.shape)
+                if not np.array_equal(got, im):
                     raise SystemExit("bench.py: decoded output differs from the input images")
 
     if args.copy_calibration:
@@ -503,7 +512,8 @@ def main():
         "vs_baseline": None,
         "dtype": "u8",
         "data": "synthetic",
-        "config": {"workload": label, "batch": n, "layout": "NCHW bf16" if fused else "HWC uint8",
+        "config": {"workload": label, "batch": n,
+                   "layout": "NCHW bf16" if fused else args.layout.upper() + " uint8",
                    "buffer_sets_rotated": args.sets,
                    "compressed_over_raw": compressed_over_raw},
         "decoded_GBps": decoded_bytes / (ms_per_step * 1e-3) / 1e9,
