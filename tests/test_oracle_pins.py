@@ -11,6 +11,7 @@ import numpy as np
 import pytest
 
 import oracle
+import oracle.build as oracle_build
 from paper_2208_08711_amd import synth
 
 import l3_testlib as tl
@@ -82,10 +83,11 @@ def test_brute_force_tiny_images(tmp_path):
     centre residual nearest-neighbour; all widths 0..8 reached.  Catches wrap
     mistakes, border mistakes and bit-order mistakes."""
     exe = str(tmp_path / "brute")
+    libdir = os.path.dirname(oracle_build.OUT)       # where the library under test lies
     subprocess.run(["g++", "-O2", "-std=c++17", "-o", exe,
                     os.path.join(HERE, "native", "brute_force.cpp"),
-                    "-L" + os.path.join(ROOT, "oracle"), "-ll3_oracle",
-                    "-Wl,-rpath," + os.path.join(ROOT, "oracle")], check=True)
+                    "-I" + os.path.join(ROOT, "oracle"), "-L" + libdir, "-ll3_oracle",
+                    "-Wl,-rpath," + libdir], check=True)
     out = subprocess.run([exe, "all"], capture_output=True, text=True, timeout=600)
     assert out.returncode == 0, out.stdout
     status, cases, widths = out.stdout.split()
