@@ -308,6 +308,66 @@ def test_many_calls_reuse_slots(l3, ctx):
             assert np.array_equal(t.cpu().numpy().reshape(im.shape), im)
 
 
+def test_two_contexts_two_streams_and_one_context_on_alternating_streams(l3, ctx):
+    """Calls of two contexts on two streams, enqueued alternately without waiting, and then
+    one context switching between the two streams from call to call; batches of 5 images
+    (descriptors inside the kernel arguments) and of 40 (descriptor table through the
+    staging slots); the fused path as well, whose table of normalised values is cached per
+    slot.  Every output is checked."""
+    small = [synth.cosine_field(1300 + k, 200 + 7 * k, 90 + 5 * k) for k in range(5)]
+    large = [synth.gradient_noise(1320 + k, 40 + k, 33 + (k % 7), 2.0) for k in range(40)]
+    other = l3.Context(0)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    try:
+        work = []
+        for images in (small, large):
+            files = [oracle.encode(im, 32) for im in images]
+            infos = [l3.peek_header(f) for f in files]
+            dfiles, keep = upload_files(files)
+            work.append((images, infos, dfiles, keep))
+        torch.cuda.synchronize()
+        results = []
+        for rep in range(10):
+            for which, (images, infos, dfiles, keep) in enumerate(work):
+                # first half: each context keeps its stream; second half: one context, both streams
+                c = (ctx, other)[(rep + which) % 2] if rep < 5 else ctx
+                st = streams[(rep + which) % 2]
+                outs = [torch.full((im.shape[0], im.shape[1] * 3), 0xEE, dtype=torch.uint8, device="cuda")
+                        for im in images]
+                status = torch.full((len(images),), 0x55, dtype=torch.int32, device="cuda")
+                st.wait_stream(torch.cuda.current_stream())      # the fills above
+                print(f"two streams: rep={rep} images={len(images)}", flush=True)
+                l3.decode_batch(c, dfiles, infos, outs, status=status, stream=st)
+                results.append((images, outs, status))
+        # the fused path from both streams with different constants each time
+        files = [oracle.encode(im, 32) for im in small]
+        infos = [l3.peek_header(f) for f in files]
+        dfiles, keep2 = upload_files(files)
+        crops = [(3 * k, 2 * k, k & 1) for k in range(len(small))]
+        fused = []
+        for rep in range(6):
+            mean = [0.1 * rep, 0.5, 0.25]
+            stdv = [0.5, 0.2 + 0.1 * rep, 1.0]
+            out = torch.full((len(small), 3, 64, 64), -1, dtype=torch.int16, device="cuda")
+            st = streams[rep % 2]
+            st.wait_stream(torch.cuda.current_stream())
+            l3.decode_crop_normalize_batch(ctx, dfiles, infos, crops, 64, 64, mean, stdv, out,
+                                           dtype=l3.BF16, stream=st)
+            fused.append((mean, stdv, out))
+        torch.cuda.synchronize()
+        for images, outs, status in results:
+            assert (status.cpu().numpy() == 0).all()
+            for t, im in zip(outs, images):
+                assert np.array_equal(t.cpu().numpy().reshape(im.shape), im)
+        for mean, stdv, out in fused:
+            got = out.cpu().numpy().view(np.uint16)
+            for i, (im, (x0, y0, flip)) in enumerate(zip(small, crops)):
+                want = oracle.crop_normalize(im, x0, y0, flip, 64, 64, mean, stdv, 0)
+                assert np.array_equal(got[i], want), (mean, stdv, i)
+    finally:
+        other.close()
+
+
 # ---------------------------------------------------------------------------
 # fused crop + flip + normalise (configs[4])
 
