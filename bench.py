@@ -61,6 +61,10 @@ def make_workload(name, batch=0):
         n = batch or 32
         return synth.config3(n, width=1920, height=1080), ("FHD: %d RGB images 1920x1080, Voronoi regions + "
                                                            "texture, N=64" % n)
+    if name == "kitti":
+        n = batch or 64
+        return synth.config3(n, width=1024, height=720), ("KITTI-shaped: %d RGB images 1024x720, Voronoi regions "
+                                                          "+ texture, N=32" % n)
     if name == "imagenet":
         return synth.config2(256), "ImageNet-shaped: 256 RGB images 400-500 x 300-375, cosine field + noise, N=32"
     if name == "train224":
@@ -312,8 +316,8 @@ def main():
     ap.add_argument("--steps", type=int, default=3000)
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="cityscapes",
-                    help="cityscapes (default, the configuration the metric is quoted on), fhd, imagenet, "
-                         "uhd, train224")
+                    help="cityscapes (default, the configuration the metric is quoted on), fhd, kitti, "
+                         "imagenet, uhd, train224")
     ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
