@@ -33,6 +33,10 @@
  *     DPP wave shifts for the two pixels at the lane's edges.
  *   - The grid is one-dimensional; every XCD takes a contiguous eighth of the
  *     (image, strip) sequence, so that strips which share cache lines share an L2.
+ *   - Where TPW does not divide the patches of a row, the host numbers an image's
+ *     units in flat order: consecutive patches in row-major order, across the ends
+ *     of patch rows (all of equal height within a unit), so that lane groups idle
+ *     only in the last unit of the image.
  */
 #include <hip/hip_runtime.h>
 
@@ -148,13 +152,32 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     if (unit >= d.units) return;                                           /* whole workgroup */
 
     const uint32_t g = lane / LPT, xl = lane % LPT;
-    const uint32_t trow = unit / d.groups_x, gx = unit - trow * d.groups_x;
-    const uint32_t ty = d.tile_y_first + trow;
-    const uint32_t txr = gx * TPW + g;
-    const bool active = txr < d.tile_x_count;
-    const uint32_t tx = d.tile_x_first + (active ? txr : d.tile_x_count - 1);
-    const uint32_t x0 = tx * N, y0 = ty * N;
-    const uint32_t strip_x0 = (d.tile_x_first + gx * TPW) * N;   /* first column of the wave's strip */
+    /* Which patch this lane group decodes: (tx, ty); ty_base is the patch row of the
+     * unit's first group, the same for the whole workgroup. */
+    uint32_t tx, ty, ty_base, strip_x0 = 0;
+    bool active;
+    const bool flat_order = MODE != L3_MODE_TENSOR && PPL == 4 && d.groups_x == 0;
+    if (flat_order) {
+        const bool upper = unit < d.flat_upper_units;
+        const uint32_t first = (upper ? unit : unit - d.flat_upper_units) * TPW;
+        const uint32_t count = upper ? d.tiles_x * d.flat_upper_rows : d.tiles_x;
+        const uint32_t row_off = upper ? 0u : d.flat_upper_rows;
+        const uint32_t fl = first + g;
+        active = fl < count;
+        const uint32_t flc = active ? fl : count - 1;
+        const uint32_t qrow = flc / d.tiles_x;
+        ty = row_off + qrow;
+        tx = flc - qrow * d.tiles_x;
+        ty_base = row_off + first / d.tiles_x;
+    } else {
+        const uint32_t trow = unit / d.groups_x, gx = unit - trow * d.groups_x;
+        const uint32_t txr = gx * TPW + g;
+        active = txr < d.tile_x_count;
+        tx = d.tile_x_first + (active ? txr : d.tile_x_count - 1);
+        ty = ty_base = d.tile_y_first + trow;
+        strip_x0 = (d.tile_x_first + gx * TPW) * N;   /* first column of the wave's strip */
+    }
+    const uint32_t x0 = tx * N, y0 = ty_base * N;     /* y0: first image row of the unit's first patch */
     const uint32_t pw = min((uint32_t)N, d.width - x0);
     uint32_t ph = min((uint32_t)N, d.height - y0);           /* same for the whole workgroup */
     if (MODE == L3_MODE_TENSOR)                              /* rows below the window are not needed */
@@ -254,11 +277,18 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                       "+s"(win_x0), "+s"(win_y0), "+s"(win_flip));
     /* lane l takes the 4-pixel words l, l + 64, ... of the wave's strip; how many of
      * their pixels exist does not change from row to row */
-    uint32_t word_x[NW], word_valid[NW];
+    uint32_t word_x[NW], word_valid[NW], word_off[NW];
 #pragma unroll
     for (int pass = 0; pass < NW; ++pass) {
-        word_x[pass] = strip_x0 + 4 * (lane + 64 * pass);
-        word_valid[pass] = word_x[pass] >= img_width ? 0u : min(4u, img_width - word_x[pass]);
+        /* in flat order (NW = 1) the word is the lane's own four pixels; a group that
+         * only shadows the block's last patch writes nothing */
+        word_x[pass] = flat_order ? x0 + 4 * xl : strip_x0 + 4 * (lane + 64 * pass);
+        word_valid[pass] = (word_x[pass] >= img_width || (flat_order && !active)) ? 0u : min(4u, img_width - word_x[pass]);
+        /* byte offset of the word from the start of the output row that the unit's
+         * first patch row writes: column bytes, plus the rows by which this group's
+         * patch row lies below it (flat order; the host checked that this fits 32 bits) */
+        word_off[pass] = (MODE == L3_MODE_HWC ? 3u : 1u) * word_x[pass] +
+                         (ty - ty_base) * (uint32_t)N * (uint32_t)out_row_stride;
     }
 
     /* After the workgroup barrier: this wave writes row c of the period whose rows
@@ -283,7 +313,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                 /* row start: scalar arithmetic; the lane's 32-bit column offset goes into the
                  * store's offset register (kept opaque here so that it is not widened and
                  * added with vector instructions ahead of time) */
-                uint32_t column = x * 3u;
+                uint32_t column = word_off[pass];
                 asm volatile("" : "+v"(column));
                 global_u8* row = reinterpret_cast<global_u8*>((uintptr_t)(out_base + (uint64_t)y * out_row_stride));
                 const uint32_t o0 = pr, o1 = pg, o2 = pb;
@@ -311,7 +341,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                     const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
                     global_u8* row = reinterpret_cast<global_u8*>(
                         (uintptr_t)(out_base + (uint64_t)ch * out_plane_stride + (uint64_t)y * out_row_stride));
-                    uint32_t column = x;
+                    uint32_t column = word_off[pass];
                     asm volatile("" : "+v"(column));
                     if (nvalid == 4) {
                         __builtin_nontemporal_store(word, reinterpret_cast<global_u32_any*>(row + column));
@@ -443,7 +473,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
         } else if (DIRECT) {
             global_u8* row = reinterpret_cast<global_u8*>(
                 (uintptr_t)(out_base + (uint64_t)c * out_plane_stride + (uint64_t)y * out_row_stride));
-            uint32_t column = word_x[0];
+            uint32_t column = word_off[0];
             asm volatile("" : "+v"(column));
             if (word_valid[0] == 4) {
                 __builtin_nontemporal_store(word[0], reinterpret_cast<global_u32_any*>(row + column));
@@ -654,6 +684,13 @@ int pixels_per_lane(int n, int mode) {
     return (e && e[0] == '8' && e[1] == 0) ? 8 : 4;
 }
 
+/* L3_FLAT_ORDER=0 in the environment keeps every image on the per-row order of units
+ * (for comparisons; the flat order is never slower in measurements). */
+bool flat_order_allowed() {
+    const char* e = std::getenv("L3_FLAT_ORDER");
+    return !(e && e[0] == '0' && e[1] == 0);
+}
+
 KernelChoice pick_kernel(int n, int mode) {
     if (pixels_per_lane(n, mode) == 8) {
         if (n == 32) return choice_for_mode<32, 8>(mode);
@@ -795,6 +832,25 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
                 d->tile_x_count = d->tiles_x;
                 d->groups_x = (d->tiles_x + tpw - 1) / tpw;
                 d->units = d->groups_x * d->tiles_y;
+                /* Flat order where it saves units: patches taken in row-major order across
+                 * the ends of patch rows.  It needs the kernel with 4 pixels per lane, and
+                 * the lanes' 32-bit byte offsets must reach tpw patch rows down. */
+                const uint64_t reach = (uint64_t)(tpw + 1) * np * d->row_stride + 3ull * d->width;
+                const uint64_t all = (uint64_t)d->tiles_x * d->tiles_y;
+                if (flat_order_allowed() && pixels_per_lane(kClasses[k], mode) == 4 && reach < 0xFFFFFFFFull &&
+                    all < 0x7FFFFFFFull) {
+                    const uint32_t upper_rows =
+                        (d->height % np != 0 && d->tiles_y > 1) ? d->tiles_y - 1 : d->tiles_y;
+                    const uint32_t upper_units = (uint32_t)(((uint64_t)d->tiles_x * upper_rows + tpw - 1) / tpw);
+                    const uint32_t units =
+                        upper_units + (upper_rows < d->tiles_y ? (d->tiles_x + tpw - 1) / tpw : 0u);
+                    if (units < d->units) {
+                        d->groups_x = 0;
+                        d->units = units;
+                        d->flat_upper_rows = upper_rows;
+                        d->flat_upper_units = upper_units;
+                    }
+                }
             }
             if (d->units > max_units[k]) max_units[k] = d->units;
         }

@@ -24,10 +24,16 @@ struct L3ImageDesc {
     uint32_t status_index;          /* which d_status word belongs to this image */
     uint32_t tile_x_first, tile_y_first; /* first patch column / row to decode */
     uint32_t tile_x_count;               /* patch columns to decode */
-    uint32_t groups_x;                   /* wave work units per patch row */
-    uint32_t units;                      /* groups_x * patch rows to decode */
+    uint32_t groups_x;                   /* wave work units per patch row; 0: flat order (below) */
+    uint32_t units;                      /* work units of this image */
     int32_t crop_x0, crop_y0;            /* tensor mode: window origin */
     uint32_t flip;                       /* tensor mode: mirror inside the window */
+    /* Flat order (pixel modes): a unit takes consecutive patches in row-major order, also
+     * across the end of a patch row, so that only the last unit of a block has idle lane
+     * groups.  The patch rows of full height form the upper block; a shorter last row is
+     * a block of its own, so that all patches of a unit have the same number of rows. */
+    uint32_t flat_upper_rows;            /* patch rows in the upper block */
+    uint32_t flat_upper_units;           /* units of the upper block */
     uint32_t pad_;
 };
 
