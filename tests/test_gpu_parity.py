@@ -219,6 +219,20 @@ def test_both_lane_widths(l3, ctx, ppl, monkeypatch):
         tensor_case(l3, ctx, [im] * len(crops), crops, 224, 0, patch=patch)
 
 
+@pytest.mark.parametrize("flat", ["1", "0"])
+def test_units_across_patch_rows(l3, ctx, flat, monkeypatch):
+    """Shapes whose patch rows do not fill whole work units, so that the library numbers the
+    units in flat order and a unit's patches lie in several patch rows (down to one patch per
+    row); with and without a shorter last patch row; both layouts, padded rows.  The same
+    with the flat order switched off."""
+    monkeypatch.setenv("L3_FLAT_ORDER", flat)
+    shapes = [(40, 300), (32, 257), (70, 129), (33, 64), (450, 337), (97, 96), (200, 33), (130, 260)]
+    images = [synth.cosine_field(1400 + k, w, h) for k, (w, h) in enumerate(shapes)]
+    for patch in (32, 64, 128):
+        for layout in ("hwc", "chw"):
+            check_batch(l3, ctx, images, patch=patch, layout=layout, pad_cols=5)
+
+
 def test_large_image_and_odd_output_address(l3, ctx):
     """A 5760x3840 image (the largest size in the paper's Table "compratio") with the
     default N = 128, decoded into a buffer that starts at an odd address with an odd
