@@ -226,7 +226,8 @@ def test_units_across_patch_rows(l3, ctx, flat, monkeypatch):
     row); with and without a shorter last patch row; both layouts, padded rows.  The same
     with the flat order switched off."""
     monkeypatch.setenv("L3_FLAT_ORDER", flat)
-    shapes = [(40, 300), (32, 257), (70, 129), (33, 64), (450, 337), (97, 96), (200, 33), (130, 260)]
+    shapes = [(40, 300), (32, 257), (70, 129), (33, 64), (450, 337), (97, 96), (200, 33), (130, 260),
+              (1, 3000), (3, 1025)]
     images = [synth.cosine_field(1400 + k, w, h) for k, (w, h) in enumerate(shapes)]
     for patch in (32, 64, 128):
         for layout in ("hwc", "chw"):
