@@ -529,8 +529,10 @@ def main():
                      "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
                      "frac": algo_lane_ops / (launch_ms * 1e-3) / 1e12 / VALU_PEAK_TLANEOPS,
                      "traffic": traffic,
-                     "kernel": "l3_decode_kernel%s<%d, 4, %s>" % ("_args" if n <= 32 else "", patch,
-                                                               "TENSOR" if fused else args.layout.upper()),
+                     "kernel": ("l3_decode_kernel_args<%d, 4, %s, %d>" % (
+                                    patch, "TENSOR" if fused else args.layout.upper(), 32 if n <= 32 else 256)
+                                if n <= 256 else
+                                "l3_decode_kernel<%d, 4, %s>" % (patch, "TENSOR" if fused else args.layout.upper())),
                      "launch_ms": launch_ms,
                      "algorithmic_lane_ops_per_decoded_byte": ALGORITHMIC_LANE_OPS_PER_DECODED_BYTE,
                      "hbm": {"achieved": algo_bytes / (launch_ms * 1e-3) / 1e9,

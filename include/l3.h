@@ -139,7 +139,7 @@ typedef enum {
  *             file (beyond the 15 bytes above).
  *   stream    a hipStream_t (NULL = the default stream).  The call returns after
  *             enqueueing; completion is observed on the stream.
- * A batch with at most 32 images of each patch size carries its descriptors in the
+ * A batch with at most 256 images of each patch size carries its descriptors in the
  * kernel arguments: such a call makes no copy, waits for nothing and (once the context
  * has served a batch of that size) allocates nothing, so it can be captured into a HIP
  * graph; the captured launches keep the pointers and sizes of the capture.  Larger

@@ -28,6 +28,9 @@ struct l3_ctx {
     float table_key[kSlots][7] = {};      /* mean, stdv, dtype the slot's table was built with */
     bool table_valid[kSlots] = {};
     hipStream_t table_stream[kSlots] = {};  /* stream that built it (another stream rebuilds) */
+    hipEvent_t table_done[kSlots] = {};     /* the kernels that read the table have finished */
+    bool table_pending[kSlots] = {};
+    int table_cur = 0;                      /* the table the last fused call used */
     hipEvent_t done[kSlots] = {};         /* the slot's kernels have finished */
     bool pending[kSlots] = {};
     int next = 0;

@@ -582,15 +582,17 @@ __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel(
     decode_unit<N, PPL, MODE>(descs[image], unit, status, crop_w, crop_h, lut);
 }
 
-/* ...or, for small batches, inside the kernel arguments: no upload, no dependency
- * on a copy, so consecutive calls run back to back. */
-constexpr int kArgDescs = 32;
-struct DescPack { L3ImageDesc d[kArgDescs]; };
-static_assert(sizeof(DescPack) + 64 <= 4096, "kernel argument segment");
+/* ...or inside the kernel arguments: no upload, no dependency on a copy, so consecutive
+ * calls run back to back.  Two capacities, so that small batches do not carry a large
+ * argument block (the runtime accepts argument blocks of at least 64 KB). */
+constexpr int kArgDescsSmall = 32, kArgDescs = 256;
+template <int CAP>
+struct DescPack { L3ImageDesc d[CAP]; };
+static_assert(sizeof(DescPack<kArgDescs>) + 64 <= 32768, "kernel argument segment");
 
-template <int N, int PPL, int MODE>
+template <int N, int PPL, int MODE, int CAP>
 __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel_args(
-    const DescPack pack, uint32_t units_per_image, uint32_t images, uint32_t* __restrict__ status,
+    const DescPack<CAP> pack, uint32_t units_per_image, uint32_t images, uint32_t* __restrict__ status,
     uint32_t crop_w, uint32_t crop_h, const uint16_t* __restrict__ lut) {
     uint32_t image, unit;
     if (!take_work(units_per_image, images, image, unit)) return;
@@ -643,12 +645,15 @@ __global__ void l3_prepare_kernel(const uint64_t* __restrict__ pinned_src, uint6
 
 typedef void (*decode_kernel_t)(const L3ImageDesc*, uint32_t, uint32_t, uint32_t*, uint32_t, uint32_t,
                                 const uint16_t*);
-typedef void (*decode_kernel_args_t)(const DescPack, uint32_t, uint32_t, uint32_t*, uint32_t, uint32_t,
-                                     const uint16_t*);
+typedef void (*decode_kernel_args_small_t)(const DescPack<kArgDescsSmall>, uint32_t, uint32_t, uint32_t*,
+                                           uint32_t, uint32_t, const uint16_t*);
+typedef void (*decode_kernel_args_t)(const DescPack<kArgDescs>, uint32_t, uint32_t, uint32_t*, uint32_t,
+                                     uint32_t, const uint16_t*);
 
 struct KernelChoice {
     decode_kernel_t table;        /* descriptors in a device table */
-    decode_kernel_args_t args;    /* descriptors in the kernel arguments */
+    decode_kernel_args_small_t args_small;   /* descriptors in the kernel arguments, up to 32 */
+    decode_kernel_args_t args;               /* up to 256 */
     int tiles_per_wave;
 };
 
@@ -659,15 +664,18 @@ KernelChoice choice_for_mode(int mode) {
     switch (mode) {
         case L3_MODE_HWC:
             k.table = l3_decode_kernel<N, PPL, L3_MODE_HWC>;
-            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_HWC>;
+            k.args_small = l3_decode_kernel_args<N, PPL, L3_MODE_HWC, kArgDescsSmall>;
+            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_HWC, kArgDescs>;
             break;
         case L3_MODE_CHW:
             k.table = l3_decode_kernel<N, PPL, L3_MODE_CHW>;
-            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_CHW>;
+            k.args_small = l3_decode_kernel_args<N, PPL, L3_MODE_CHW, kArgDescsSmall>;
+            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_CHW, kArgDescs>;
             break;
         default:
             k.table = l3_decode_kernel<N, PPL, L3_MODE_TENSOR>;
-            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_TENSOR>;
+            k.args_small = l3_decode_kernel_args<N, PPL, L3_MODE_TENSOR, kArgDescsSmall>;
+            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_TENSOR, kArgDescs>;
             break;
     }
     return k;
@@ -774,7 +782,9 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     if ((size_t)n > ctx->scratch_cap) {
         size_t cap = 256;
         while (cap < (size_t)n) cap *= 2;
-        L3ImageDesc* grown = static_cast<L3ImageDesc*>(std::realloc(ctx->scratch, cap * sizeof(L3ImageDesc)));
+        /* kArgDescs spare entries: a launch may read a whole argument block from any descriptor on */
+        L3ImageDesc* grown = static_cast<L3ImageDesc*>(
+            std::realloc(ctx->scratch, (cap + kArgDescs) * sizeof(L3ImageDesc)));
         if (!grown) return L3_ERR_DEVICE;
         ctx->scratch = grown;
         ctx->scratch_cap = cap;
@@ -789,6 +799,7 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     for (int k = 0; k < 3; ++k) {
         class_begin[k] = filled;
         const int tpw = pick_kernel(kClasses[k], mode).tiles_per_wave;
+        const bool flat_ok = flat_order_allowed() && pixels_per_lane(kClasses[k], mode) == 4;
         for (int i = 0; i < n; ++i) {
             if (k == 0) {   /* validate everything before anything is enqueued */
                 L3ImageDesc probe;
@@ -837,8 +848,7 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
                  * the lanes' 32-bit byte offsets must reach tpw patch rows down. */
                 const uint64_t reach = (uint64_t)(tpw + 1) * np * d->row_stride + 3ull * d->width;
                 const uint64_t all = (uint64_t)d->tiles_x * d->tiles_y;
-                if (flat_order_allowed() && pixels_per_lane(kClasses[k], mode) == 4 && reach < 0xFFFFFFFFull &&
-                    all < 0x7FFFFFFFull) {
+                if (flat_ok && reach < 0xFFFFFFFFull && all < 0x7FFFFFFFull) {
                     const uint32_t upper_rows =
                         (d->height % np != 0 && d->tiles_y > 1) ? d->tiles_y - 1 : d->tiles_y;
                     const uint32_t upper_units = (uint32_t)(((uint64_t)d->tiles_x * upper_rows + tpw - 1) / tpw);
@@ -860,12 +870,14 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     /* Small batches travel inside the kernel arguments; larger ones through a device
      * table that a small kernel on the caller's stream pulls from pinned host memory. */
     bool in_args = true;
-    for (int k = 0; k < 3; ++k)
-        if (class_begin[k + 1] - class_begin[k] > kArgDescs) in_args = false;
+    for (int k = 0; k < 3; ++k) {
+        const uint64_t count = (uint64_t)(class_begin[k + 1] - class_begin[k]);
+        if (count > (uint64_t)kArgDescs || count * max_units[k] > 0x7FFFFF00ull) in_args = false;
+    }
 
     int slot = -1;
     L3ImageDesc* d_descs = nullptr;
-    if (!in_args || mode == L3_MODE_TENSOR) {
+    if (!in_args) {
         st = ensure_capacity(ctx, (size_t)n);
         if (st != L3_OK) return st;
         slot = ctx->next;
@@ -889,19 +901,39 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     }
     const uint16_t* table = nullptr;
     if (mode == L3_MODE_TENSOR) {
-        /* The slot's table is rebuilt only when the constants differ from the ones it was
-         * built with (the slot's earlier kernels have finished: waited for above).  The
-         * build runs on this call's stream, ahead of the kernel that reads the table. */
+        /* The table of the 256 normalised values per channel.  As long as the constants
+         * and the stream stay what they were, calls share the current table and nothing
+         * is recorded or waited for.  Otherwise the current table is left to the kernels
+         * that still read it and the next of kSlots tables is built on this call's stream,
+         * ahead of the kernel that reads it; a table is reused only after the kernels that
+         * read it have finished (an event on the unchanged stream; a device-wide wait
+         * when the stream changed too, whose handle may no longer exist). */
         const float key[7] = {mean[0], mean[1], mean[2], stdv[0], stdv[1], stdv[2], (float)dtype};
-        if (!ctx->table_valid[slot] || std::memcmp(ctx->table_key[slot], key, sizeof key) != 0 ||
-            ctx->table_stream[slot] != stream) {
+        int ts = ctx->table_cur;
+        if (!ctx->table_valid[ts] || std::memcmp(ctx->table_key[ts], key, sizeof key) != 0 ||
+            ctx->table_stream[ts] != stream) {
+            if (ctx->table_valid[ts]) {
+                if (ctx->table_stream[ts] == stream) {
+                    if (hipEventRecord(ctx->table_done[ts], stream) != hipSuccess) return L3_ERR_DEVICE;
+                    ctx->table_pending[ts] = true;
+                } else {
+                    if (hipDeviceSynchronize() != hipSuccess) return L3_ERR_DEVICE;
+                    for (int s = 0; s < kSlots; ++s) ctx->table_pending[s] = false;
+                }
+            }
+            ts = (ts + 1) % kSlots;
+            if (ctx->table_pending[ts]) {
+                if (hipEventSynchronize(ctx->table_done[ts]) != hipSuccess) return L3_ERR_DEVICE;
+                ctx->table_pending[ts] = false;
+            }
             hipLaunchKernelGGL(l3_build_table_kernel, dim3(3), dim3(256), 0, stream, mean[0], mean[1],
-                               mean[2], stdv[0], stdv[1], stdv[2], dtype, ctx->d_table[slot]);
-            std::memcpy(ctx->table_key[slot], key, sizeof key);
-            ctx->table_valid[slot] = true;
-            ctx->table_stream[slot] = stream;
+                               mean[2], stdv[0], stdv[1], stdv[2], dtype, ctx->d_table[ts]);
+            std::memcpy(ctx->table_key[ts], key, sizeof key);
+            ctx->table_valid[ts] = true;
+            ctx->table_stream[ts] = stream;
+            ctx->table_cur = ts;
         }
-        table = ctx->d_table[slot];
+        table = ctx->d_table[ts];
     }
     for (int k = 0; k < 3; ++k) {
         const int count = class_begin[k + 1] - class_begin[k];
@@ -909,12 +941,25 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         const uint32_t gx = max_units[k];
         /* one-dimensional grid, rounded up to a multiple of 8 (see take_work) */
         const auto grid_for = [gx](uint64_t images) { return (uint32_t)((gx * images + 7) / 8 * 8); };
-        if (in_args) {
-            DescPack pack;
+        if (in_args && count <= kArgDescsSmall) {
+            DescPack<kArgDescsSmall> pack;
             std::memcpy(pack.d, stage + class_begin[k], (size_t)count * sizeof(L3ImageDesc));
-            hipLaunchKernelGGL(pick_kernel(kClasses[k], mode).args, dim3(grid_for((uint64_t)count)),
+            hipLaunchKernelGGL(pick_kernel(kClasses[k], mode).args_small, dim3(grid_for((uint64_t)count)),
                                dim3(kBlockThreads), 0, stream, pack, gx, (uint32_t)count, d_status, crop_w,
                                crop_h, table);
+            continue;
+        }
+        if (in_args) {
+            /* 28 KB of arguments: handed over by address, straight from the staging array
+             * (which has kArgDescs spare entries behind the last descriptor), so that the
+             * block is copied once, by the launch, and never sits on the stack */
+            uint32_t gx_arg = gx, count_arg = (uint32_t)count;
+            void* kernel_args[7] = {stage + class_begin[k], &gx_arg, &count_arg, &d_status,
+                                    &crop_w, &crop_h, &table};
+            if (hipLaunchKernel(reinterpret_cast<const void*>(pick_kernel(kClasses[k], mode).args),
+                                dim3(grid_for((uint64_t)count)), dim3(kBlockThreads), kernel_args, 0,
+                                stream) != hipSuccess)
+                return L3_ERR_DEVICE;
             continue;
         }
         decode_kernel_t kern = pick_kernel(kClasses[k], mode).table;
@@ -952,6 +997,7 @@ l3_status l3_ctx_create(l3_ctx** out, int device) {
     ctx->device = device;
     for (int s = 0; s < kSlots; ++s) {
         if (hipEventCreateWithFlags(&ctx->done[s], hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&ctx->table_done[s], hipEventDisableTiming) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&ctx->d_table[s]), 768 * sizeof(uint16_t)) !=
                 hipSuccess) {
             l3_ctx_destroy(ctx);
@@ -965,9 +1011,13 @@ l3_status l3_ctx_create(l3_ctx** out, int device) {
 void l3_ctx_destroy(l3_ctx* ctx) {
     if (!ctx) return;
     DeviceGuard guard(ctx->device);
+    /* kernels of the last fused calls may still read the current table */
+    if (ctx->table_valid[ctx->table_cur]) (void)hipDeviceSynchronize();
     for (int s = 0; s < kSlots; ++s) {
         if (ctx->pending[s]) (void)hipEventSynchronize(ctx->done[s]);
         if (ctx->done[s]) (void)hipEventDestroy(ctx->done[s]);
+        if (ctx->table_pending[s]) (void)hipEventSynchronize(ctx->table_done[s]);
+        if (ctx->table_done[s]) (void)hipEventDestroy(ctx->table_done[s]);
         if (ctx->d_table[s]) (void)hipFree(ctx->d_table[s]);
     }
     release_slots(ctx);
