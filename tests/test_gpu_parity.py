@@ -308,8 +308,9 @@ def test_host_errors_enqueue_nothing(l3, ctx):
 
 
 def test_many_calls_reuse_slots(l3, ctx):
-    """More calls in flight than staging slots; results stay correct."""
-    images = synth.config2(6)
+    """More calls in flight than staging slots (batches of 300 images go through the pinned
+    descriptor tables); results stay correct."""
+    images = [synth.cosine_field(1800 + k, 40 + (k % 9), 35 + (k % 4)) for k in range(300)]
     files = [oracle.encode(im) for im in images]
     infos = [l3.peek_header(f) for f in files]
     dfiles, keep = upload_files(files)
@@ -326,16 +327,17 @@ def test_many_calls_reuse_slots(l3, ctx):
 def test_two_contexts_two_streams_and_one_context_on_alternating_streams(l3, ctx):
     """Calls of two contexts on two streams, enqueued alternately without waiting, and then
     one context switching between the two streams from call to call; batches of 5 images
-    (descriptors inside the kernel arguments) and of 40 (descriptor table through the
-    staging slots); the fused path as well, whose table of normalised values is cached per
-    slot.  Every output is checked."""
+    (descriptors inside the small kernel-argument block), of 40 (the large block) and of 300
+    (descriptor table through the staging slots); the fused path as well, whose table of
+    normalised values is kept across calls.  Every output is checked."""
     small = [synth.cosine_field(1300 + k, 200 + 7 * k, 90 + 5 * k) for k in range(5)]
     large = [synth.gradient_noise(1320 + k, 40 + k, 33 + (k % 7), 2.0) for k in range(40)]
+    huge = [synth.gradient_noise(1700 + k, 33 + (k % 5), 34 + (k % 3), 2.0) for k in range(300)]
     other = l3.Context(0)
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
     try:
         work = []
-        for images in (small, large):
+        for images in (small, large, huge):
             files = [oracle.encode(im, 32) for im in images]
             infos = [l3.peek_header(f) for f in files]
             dfiles, keep = upload_files(files)
