@@ -457,12 +457,13 @@ def test_fused_crop_edges(l3, ctx):
     assert np.array_equal(out.cpu().numpy().view(np.uint16)[0], want)
 
 
-def test_decode_batch_replayed_from_a_captured_graph(l3, ctx):
-    """Batches of at most 32 images carry their descriptors in the kernel arguments and
-    allocate nothing once the context is warm, so the call can be captured into a HIP
-    graph.  Every replay (with eager work and synchronisation between them) must give the
-    eager result."""
-    images = [synth.voronoi_scene(3300 + k, 300 + 7 * k, 150 + 3 * k, sites=9) for k in range(5)]
+@pytest.mark.parametrize("count", [5, 40])
+def test_decode_batch_replayed_from_a_captured_graph(l3, ctx, count):
+    """Batches of at most 256 images carry their descriptors in the kernel arguments (a small
+    block up to 32 images, a large one beyond) and allocate nothing once the context is warm,
+    so the call can be captured into a HIP graph.  Every replay (with eager work and
+    synchronisation between them) must give the eager result."""
+    images = [synth.voronoi_scene(3300 + k, 100 + 7 * (k % 9), 70 + 3 * (k % 11), sites=9) for k in range(count)]
     files = [oracle.encode(im) for im in images]
     infos = [l3.peek_header(f) for f in files]
     dfiles, keep = upload_files(files)
