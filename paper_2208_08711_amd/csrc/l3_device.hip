@@ -839,28 +839,7 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
                 d->out = items[i].d_out;
                 d->row_stride = items[i].out_row_stride;
                 d->plane_stride = (uint64_t)items[i].out_row_stride * d->height;
-                d->tile_x_first = d->tile_y_first = 0;
-                d->tile_x_count = d->tiles_x;
-                d->groups_x = (d->tiles_x + tpw - 1) / tpw;
-                d->units = d->groups_x * d->tiles_y;
-                /* Flat order where it saves units: patches taken in row-major order across
-                 * the ends of patch rows.  It needs the kernel with 4 pixels per lane, and
-                 * the lanes' 32-bit byte offsets must reach tpw patch rows down. */
-                const uint64_t reach = (uint64_t)(tpw + 1) * np * d->row_stride + 3ull * d->width;
-                const uint64_t all = (uint64_t)d->tiles_x * d->tiles_y;
-                if (flat_ok && reach < 0xFFFFFFFFull && all < 0x7FFFFFFFull) {
-                    const uint32_t upper_rows =
-                        (d->height % np != 0 && d->tiles_y > 1) ? d->tiles_y - 1 : d->tiles_y;
-                    const uint32_t upper_units = (uint32_t)(((uint64_t)d->tiles_x * upper_rows + tpw - 1) / tpw);
-                    const uint32_t units =
-                        upper_units + (upper_rows < d->tiles_y ? (d->tiles_x + tpw - 1) / tpw : 0u);
-                    if (units < d->units) {
-                        d->groups_x = 0;
-                        d->units = units;
-                        d->flat_upper_rows = upper_rows;
-                        d->flat_upper_units = upper_units;
-                    }
-                }
+                l3_plan_units(d, np, (uint32_t)tpw, flat_ok);
             }
             if (d->units > max_units[k]) max_units[k] = d->units;
         }

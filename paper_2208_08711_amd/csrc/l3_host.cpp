@@ -241,3 +241,25 @@ l3_status l3_peek_header(const uint8_t* file, size_t len, l3_info* info) {
 }
 
 }  // extern "C"
+
+void l3_plan_units(L3ImageDesc* d, uint32_t patch, uint32_t tpw, bool flat_ok) {
+    d->tile_x_first = d->tile_y_first = 0;
+    d->tile_x_count = d->tiles_x;
+    d->groups_x = (d->tiles_x + tpw - 1) / tpw;
+    d->units = d->groups_x * d->tiles_y;
+    d->flat_upper_rows = d->flat_upper_units = 0;
+    /* Flat order where it saves units: patches taken in row-major order across the ends
+     * of patch rows.  The lanes' 32-bit byte offsets must reach tpw patch rows down. */
+    const uint64_t reach = (uint64_t)(tpw + 1) * patch * d->row_stride + 3ull * d->width;
+    const uint64_t all = (uint64_t)d->tiles_x * d->tiles_y;
+    if (!flat_ok || reach >= 0xFFFFFFFFull || all >= 0x7FFFFFFFull) return;
+    const uint32_t upper_rows = (d->height % patch != 0 && d->tiles_y > 1) ? d->tiles_y - 1 : d->tiles_y;
+    const uint32_t upper_units = (uint32_t)(((uint64_t)d->tiles_x * upper_rows + tpw - 1) / tpw);
+    const uint32_t units = upper_units + (upper_rows < d->tiles_y ? (d->tiles_x + tpw - 1) / tpw : 0u);
+    if (units < d->units) {
+        d->groups_x = 0;
+        d->units = units;
+        d->flat_upper_rows = upper_rows;
+        d->flat_upper_units = upper_units;
+    }
+}

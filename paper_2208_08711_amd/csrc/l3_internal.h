@@ -46,4 +46,11 @@ enum {
 
 enum { L3_MODE_HWC = 0, L3_MODE_CHW = 1, L3_MODE_TENSOR = 2 };
 
+/* Host planning for the pixel modes (whole image): deals the image's patches to work units
+ * of tpw patches.  Needs width, height, tiles_x, tiles_y and row_stride of *d; sets the
+ * tile window, groups_x, units and the flat_ fields.  Per-row order: groups_x units per
+ * patch row.  Flat order (only if flat_ok, where it saves units and the lanes' 32-bit
+ * offsets reach far enough): see the flat_ fields of L3ImageDesc.  (l3_host.cpp) */
+void l3_plan_units(L3ImageDesc* d, uint32_t patch, uint32_t tpw, bool flat_ok);
+
 #endif

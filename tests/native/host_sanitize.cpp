@@ -10,7 +10,9 @@
  *     length, and one byte short of it (must be refused, nothing written past),
  *   - files cut at every length, and files with damaged headers and offsets
  *     (Section 4.3 of arxiv 2208.08711: signature, width, height, patch size, the
- *     three offset arrays), for the validator.
+ *     three offset arrays), for the validator,
+ *   - and the host planner's dealing of patches to work units, against the mapping the
+ *     decode kernel applies to it.
  * Prints "ok <cases>" and exits 0; any finding aborts.
  */
 #include <cstdint>
@@ -21,6 +23,7 @@
 
 #include "l3.h"
 #include "l3_ablation.h"
+#include "l3_internal.h"   /* the host planner's descriptor and l3_plan_units */
 
 namespace {
 
@@ -66,6 +69,90 @@ void check_accepted(const uint8_t* f, size_t len, const l3_info& info) {
         require(off < data, "offset inside the data section", info.width, info.height, info.patch);
         prev = off;
     }
+}
+
+/* The host's dealing of patches to work units (per-row and flat order), checked against
+ * what the decode kernel does with it, written out again here: unit u, lane group g of
+ * tpw -> patch (tx, ty).  Every patch must be taken exactly once, all patches of a unit
+ * must have the same number of rows, a unit's first group must be the topmost, and the
+ * flat order must never need more units than the per-row order. */
+unsigned long check_plans() {
+    unsigned long cases = 0;
+    const uint32_t sizes[] = {1, 2, 31, 32, 33, 63, 64, 65, 96, 127, 128, 129, 200, 255, 256, 257, 450, 500, 1000, 1920, 2048};
+    const uint32_t nsizes = sizeof sizes / sizeof *sizes;
+    for (uint32_t np = 32; np <= 128; np *= 2)
+        for (uint32_t tpw = 256 / np; tpw <= 512 / np; tpw *= 2)      /* 4 and 8 pixels per lane */
+            for (uint32_t wi = 0; wi < nsizes; ++wi)
+                for (uint32_t hi = 0; hi < nsizes; ++hi)
+                    for (int flat_ok = 0; flat_ok < 2; ++flat_ok) {
+                        L3ImageDesc d;
+                        std::memset(&d, 0, sizeof d);
+                        d.width = sizes[wi];
+                        d.height = sizes[hi];
+                        d.tiles_x = (d.width + np - 1) / np;
+                        d.tiles_y = (d.height + np - 1) / np;
+                        d.row_stride = 3ull * d.width + (wi % 3);
+                        l3_plan_units(&d, np, tpw, flat_ok != 0);
+                        const uint32_t per_row = ((d.tiles_x + tpw - 1) / tpw) * d.tiles_y;
+                        require(d.units <= per_row && d.units >= 1, "unit count", d.width, d.height, np);
+                        require(flat_ok || d.groups_x != 0, "flat order only when allowed", d.width, d.height, np);
+                        std::vector<unsigned> taken((size_t)d.tiles_x * d.tiles_y, 0);
+                        for (uint32_t u = 0; u < d.units; ++u) {
+                            uint32_t base_ty = 0, rows = 0;
+                            for (uint32_t g = 0; g < tpw; ++g) {
+                                uint32_t tx, ty, ty_base;
+                                bool active;
+                                if (d.groups_x == 0) {
+                                    const bool upper = u < d.flat_upper_units;
+                                    const uint32_t first = (upper ? u : u - d.flat_upper_units) * tpw;
+                                    const uint32_t count = upper ? d.tiles_x * d.flat_upper_rows : d.tiles_x;
+                                    const uint32_t row_off = upper ? 0u : d.flat_upper_rows;
+                                    require(first < count, "unit inside its block", d.width, d.height, np);
+                                    const uint32_t fl = first + g;
+                                    active = fl < count;
+                                    const uint32_t flc = active ? fl : count - 1;
+                                    ty = row_off + flc / d.tiles_x;
+                                    tx = flc % d.tiles_x;
+                                    ty_base = row_off + first / d.tiles_x;
+                                } else {
+                                    const uint32_t trow = u / d.groups_x, gx = u % d.groups_x;
+                                    const uint32_t txr = gx * tpw + g;
+                                    active = txr < d.tile_x_count;
+                                    tx = d.tile_x_first + (active ? txr : d.tile_x_count - 1);
+                                    ty = ty_base = d.tile_y_first + trow;
+                                }
+                                require(tx < d.tiles_x && ty < d.tiles_y && ty_base <= ty, "patch inside the image",
+                                        d.width, d.height, np);
+                                const uint32_t ph = d.height - ty * np < np ? d.height - ty * np : np;
+                                if (g == 0) {
+                                    base_ty = ty_base;
+                                    rows = ph;
+                                    require(ty == ty_base, "first group is the topmost", d.width, d.height, np);
+                                }
+                                require(ty_base == base_ty && ph == rows, "one height per unit", d.width, d.height, np);
+                                /* the lane's 32-bit output offset reaches its patch row */
+                                require((uint64_t)(ty - ty_base) * np * d.row_stride + 3ull * d.width < 0xFFFFFFFFull,
+                                        "offset fits 32 bits", d.width, d.height, np);
+                                if (active) ++taken[(size_t)ty * d.tiles_x + tx];
+                            }
+                        }
+                        for (size_t k = 0; k < taken.size(); ++k)
+                            require(taken[k] == 1, "every patch exactly once", d.width, d.height, np);
+                        ++cases;
+                    }
+    /* where the offsets would not fit, the per-row order stays */
+    {
+        L3ImageDesc d;
+        std::memset(&d, 0, sizeof d);
+        d.width = 450;
+        d.height = 337;
+        d.tiles_x = 15;
+        d.tiles_y = 11;
+        d.row_stride = 1ull << 28;
+        l3_plan_units(&d, 32, 8, true);
+        require(d.groups_x == 2 && d.units == 22, "per-row order for huge strides", d.width, d.height, 32);
+    }
+    return cases;
 }
 
 }  // namespace
@@ -161,6 +248,7 @@ int main() {
             return 1;
         }
     }
+    cases += check_plans();
     std::printf("ok %lu\n", cases);
     return 0;
 }
