@@ -142,14 +142,17 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     __shared__ __attribute__((aligned(8))) uint32_t parked[PARKS][P][3][QW]; /* [buffer][row of period][channel][word] */
     __shared__ uint16_t s_lut[MODE == L3_MODE_TENSOR ? 768 : 2];
 
-    if (MODE == L3_MODE_TENSOR) {
-        for (uint32_t i = threadIdx.x; i < 768; i += kBlockThreads) s_lut[i] = lut[i];
-        __syncthreads();
-    }
-
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t c = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   /* this wave's channel */
     if (unit >= d.units) return;                                           /* whole workgroup */
+    /* the table of normalised values (first needed by the first write-out) is requested
+     * first and put into LDS behind the stream's first chunk, so that it costs no round
+     * trip of its own */
+    uint16_t lut_part[4] = {0, 0, 0, 0};
+    if (MODE == L3_MODE_TENSOR) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) lut_part[k] = lut[threadIdx.x + k * kBlockThreads];
+    }
 
     const uint32_t g = lane / LPT, xl = lane % LPT;
     /* Which patch this lane group decodes: (tx, ty); ty_base is the patch row of the
@@ -219,6 +222,11 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
         fill = CHUNK;
 #pragma unroll
         for (int t = 0; t < GPL; ++t) pf[t] = load_granule(origin, CHUNK + (t * LPT + xl) * 16, limit);
+    }
+    if (MODE == L3_MODE_TENSOR) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s_lut[threadIdx.x + k * kBlockThreads] = lut_part[k];
+        __syncthreads();
     }
     wave_lds_fence();
 
