@@ -168,6 +168,12 @@ typedef enum { L3_BF16 = 0, L3_FP16 = 1 } l3_dtype;
  * items[i].d_out / out_row_stride are ignored.  crops is a HOST array of n
  * entries; every window must lie inside its image.  mean and stdv are HOST
  * arrays of 3 floats (stdv non-zero).  Other arguments as l3_decode_batch.
+ * The context keeps a device table of the 256 values of y per channel for the
+ * constants (mean, stdv, dtype) and the stream of the last call: calls with the
+ * same constants on the same stream reuse it and wait for nothing; a call with other
+ * constants builds a new table on its stream (the host may wait for the kernels that
+ * used the table four changes back); a call on another stream waits for the device
+ * to become idle first.  Keep a context per stream where streams alternate.
  * Errors: as l3_decode_batch, plus INVALID_ARG for a window outside its image. */
 l3_status l3_decode_crop_normalize_batch(l3_ctx* ctx, const l3_item* items,
                                          const l3_crop* crops, int n,
