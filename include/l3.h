@@ -87,7 +87,7 @@ typedef struct {
     size_t   header_bytes;           /* 13 + 12 * patches_per_channel */
 } l3_info;
 
-/* Section 4.4 "the decoder first reads the header of each image": parse and
+/* Section 4.4, header parse on the host ahead of the GPU work: parse and
  * validate the header of a file held in HOST memory (`file`, `len` bytes) and
  * fill *info.  Checks the signature, non-zero sizes, that the header fits in
  * len, that the 3*P offsets start at 0, increase strictly and stay inside the
@@ -168,12 +168,14 @@ typedef enum { L3_BF16 = 0, L3_FP16 = 1 } l3_dtype;
  * items[i].d_out / out_row_stride are ignored.  crops is a HOST array of n
  * entries; every window must lie inside its image.  mean and stdv are HOST
  * arrays of 3 floats (stdv non-zero).  Other arguments as l3_decode_batch.
- * The context keeps a device table of the 256 values of y per channel for the
- * constants (mean, stdv, dtype) and the stream of the last call: calls with the
- * same constants on the same stream reuse it and wait for nothing; a call with other
- * constants builds a new table on its stream (the host may wait for the kernels that
- * used the table four changes back); a call on another stream waits for the device
- * to become idle first.  Keep a context per stream where streams alternate.
+ * The context keeps device tables of the 256 values of y per channel, one per pair of
+ * constants (mean, stdv, dtype) and stream in use, at most four: a call that finds its
+ * pair builds nothing and waits for nothing; a new pair builds its table on the call's
+ * stream and, where it takes over the table of a pair last used on another stream, makes
+ * its stream wait on the device for the kernels that still read it (the host never
+ * waits).  Under stream capture the table is built inside the captured work, into a table
+ * of its own, so that a replayed graph stands alone; captured fused calls of one context
+ * share that table and must not run concurrently with different constants.
  * Errors: as l3_decode_batch, plus INVALID_ARG for a window outside its image. */
 l3_status l3_decode_crop_normalize_batch(l3_ctx* ctx, const l3_item* items,
                                          const l3_crop* crops, int n,

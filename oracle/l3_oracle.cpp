@@ -29,8 +29,8 @@ void store_u32le(uint8_t* p, uint32_t v) {
     p[3] = (uint8_t)(v >> 24);
 }
 
-/* Section 4.2, base-delta: "the first four bits ... the following eight bits
- * ... then the deltas" -- a stream of bit fields.  Bit k lives in byte k/8 at
+/* Section 4.2, base-delta: per row a 4-bit width, an 8-bit base, then the deltas
+ * at that width -- a stream of bit fields.  Bit k lives in byte k/8 at
  * bit position k%8; a field's least significant bit is written first. */
 struct BitWriter {
     std::vector<uint8_t> bytes;

@@ -24,13 +24,18 @@ struct l3_ctx {
     size_t cap = 0;                       /* descriptors per slot */
     L3ImageDesc* h_stage[kSlots] = {};    /* pinned host */
     L3ImageDesc* d_descs[kSlots] = {};    /* device */
-    uint16_t* d_table[kSlots] = {};       /* device: 768-entry normalisation table */
+    bool flat_order = true;               /* flat order of work units allowed (L3_FLAT_ORDER=0 at creation: off) */
+    /* Fused path: tables of the 256 normalised values per channel, one slot per (constants,
+     * stream) pair in use; table_used[s] is recorded behind every call that reads slot s, so
+     * that a call on another stream that takes the slot over can wait for it on the device. */
+    uint16_t* d_table[kSlots] = {};       /* device: 768 entries each */
+    uint16_t* d_table_capture = nullptr;  /* device: the table of calls made under stream capture */
     float table_key[kSlots][7] = {};      /* mean, stdv, dtype the slot's table was built with */
     bool table_valid[kSlots] = {};
-    hipStream_t table_stream[kSlots] = {};  /* stream that built it (another stream rebuilds) */
-    hipEvent_t table_done[kSlots] = {};     /* the kernels that read the table have finished */
-    bool table_pending[kSlots] = {};
-    int table_cur = 0;                      /* the table the last fused call used */
+    hipStream_t table_stream[kSlots] = {};
+    hipEvent_t table_used[kSlots] = {};
+    bool table_used_valid[kSlots] = {};
+    int table_cur = 0;                    /* the slot the last fused call used */
     hipEvent_t done[kSlots] = {};         /* the slot's kernels have finished */
     bool pending[kSlots] = {};
     int next = 0;

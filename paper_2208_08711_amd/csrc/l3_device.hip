@@ -245,7 +245,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     }
 
     /* what the arithmetic of a row needs from its base-delta record */
-    uint32_t w, w2, w3, base2, xbit[NW], wmax = 0;
+    uint32_t w, w2, K, base2, xbit[NW], wmax = 0;
     uint32_t xwhere[NW];   /* LDS addresses of the words holding this lane's deltas of the open row */
     uint32_t hwhere;       /* LDS address of the words holding the record after the open row */
     const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)ring;
@@ -269,7 +269,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
         hwhere = ring_where<RING>(ring_lds, bitpos);
         w = wr;
         w2 = wr + wr;
-        w3 = w2 + wr;
+        K = 0xFFFFFFFFu << wr;
         base2 = base | (base << 16);
     };
 
@@ -457,13 +457,18 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
         uint32_t word[NW];
 #pragma unroll
         for (int k = 0; k < NW; ++k) {
+            /* The lane's four deltas d0..d3 sit in the low 4w bits of x.  Y holds the two
+             * halves of that field in its 16-bit halves: (d0 | d1 << w, d2 | d3 << w).  A
+             * packed shift by w leaves (d1, d3); taking that, times 2^w, off Y leaves
+             * (d0, d2): K = -(2^w) mod 2^16 turns it into one packed multiply-add. */
             const uint32_t x = ring_align(xw[k], xbit[k]);
-            const uint32_t d0 = __builtin_amdgcn_ubfe(x, 0, w);
-            const uint32_t d1 = __builtin_amdgcn_ubfe(x, w, w);
-            const uint32_t d2 = __builtin_amdgcn_ubfe(x, w2, w);
-            const uint32_t d3 = __builtin_amdgcn_ubfe(x, w3, w);
-            prev[2 * k] = (pred[2 * k] + (d0 | (d2 << 16)) + base2) & 0x00FF00FFu;
-            prev[2 * k + 1] = (pred[2 * k + 1] + (d1 | (d3 << 16)) + base2) & 0x00FF00FFu;
+            const uint32_t f01 = __builtin_amdgcn_ubfe(x, 0, w2);
+            const uint32_t f23 = __builtin_amdgcn_ubfe(x, w2, w2);
+            const uint32_t Y = f01 | (f23 << 16);
+            const uint32_t B = pk_lshr_b16_by_low(w, Y);
+            const uint32_t A = pk_mad_u16_by_low(B, K, Y);   /* before the 32-bit sums: Y's halves are full */
+            prev[2 * k] = (A + pred[2 * k] + base2) & 0x00FF00FFu;
+            prev[2 * k + 1] = (B + pred[2 * k + 1] + base2) & 0x00FF00FFu;
             if (MODE != L3_MODE_HWC)
                 word[k] = __builtin_amdgcn_perm(prev[2 * k + 1], prev[2 * k], 0x06020400u);   /* p0 p1 p2 p3 */
         }
@@ -689,33 +694,15 @@ KernelChoice choice_for_mode(int mode) {
     return k;
 }
 
-/* Pixels per lane.  Both variants are kept: on MI355X 4 measured faster on every
- * benchmark workload (more, smaller waves hide latency better than the 12 % fewer
- * vector instructions of 8 buy).  L3_PIXELS_PER_LANE=8 in the environment selects
- * the other one. */
-int pixels_per_lane(int n, int mode) {
-    (void)n;
-    (void)mode;
-    const char* e = std::getenv("L3_PIXELS_PER_LANE");
-    return (e && e[0] == '8' && e[1] == 0) ? 8 : 4;
-}
-
-/* L3_FLAT_ORDER=0 in the environment keeps every image on the per-row order of units
- * (for comparisons; the flat order is never slower in measurements). */
-bool flat_order_allowed() {
-    const char* e = std::getenv("L3_FLAT_ORDER");
-    return !(e && e[0] == '0' && e[1] == 0);
-}
+/* The kernels are written for NW = PPL / 4 words of four pixels per lane; the library is
+ * built with PPL = 4 (one word): 8 pixels per lane issue 12 % fewer vector instructions but
+ * halve the number of waves, and measured slower on every workload. */
+constexpr int kPixelsPerLane = 4;
 
 KernelChoice pick_kernel(int n, int mode) {
-    if (pixels_per_lane(n, mode) == 8) {
-        if (n == 32) return choice_for_mode<32, 8>(mode);
-        if (n == 64) return choice_for_mode<64, 8>(mode);
-        return choice_for_mode<128, 8>(mode);
-    }
-    if (n == 32) return choice_for_mode<32, 4>(mode);
-    if (n == 64) return choice_for_mode<64, 4>(mode);
-    return choice_for_mode<128, 4>(mode);
+    if (n == 32) return choice_for_mode<32, kPixelsPerLane>(mode);
+    if (n == 64) return choice_for_mode<64, kPixelsPerLane>(mode);
+    return choice_for_mode<128, kPixelsPerLane>(mode);
 }
 
 }  // namespace
@@ -807,7 +794,7 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     for (int k = 0; k < 3; ++k) {
         class_begin[k] = filled;
         const int tpw = pick_kernel(kClasses[k], mode).tiles_per_wave;
-        const bool flat_ok = flat_order_allowed() && pixels_per_lane(kClasses[k], mode) == 4;
+        const bool flat_ok = ctx->flat_order;
         for (int i = 0; i < n; ++i) {
             if (k == 0) {   /* validate everything before anything is enqueued */
                 L3ImageDesc probe;
@@ -887,40 +874,49 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
                            (uint32_t)n, 0u);
     }
     const uint16_t* table = nullptr;
+    int table_slot = -1;   /* the cache slot this call reads, if any */
     if (mode == L3_MODE_TENSOR) {
-        /* The table of the 256 normalised values per channel.  As long as the constants
-         * and the stream stay what they were, calls share the current table and nothing
-         * is recorded or waited for.  Otherwise the current table is left to the kernels
-         * that still read it and the next of kSlots tables is built on this call's stream,
-         * ahead of the kernel that reads it; a table is reused only after the kernels that
-         * read it have finished (an event on the unchanged stream; a device-wide wait
-         * when the stream changed too, whose handle may no longer exist). */
+        /* The table of the 256 normalised values per channel, built by a small kernel on the
+         * call's stream ahead of the kernel that reads it.
+         *  - under stream capture: always built, into a table of its own, so that the graph
+         *    holds the build and replays stand alone.
+         *  - otherwise cached: a slot per (constants, stream) pair; a call that finds its pair
+         *    builds nothing.  A pair that is not there takes the next slot in turn; the kernels
+         *    that still read that slot on another stream are waited for on the device (event
+         *    recorded behind every cached call), never on the host. */
         const float key[7] = {mean[0], mean[1], mean[2], stdv[0], stdv[1], stdv[2], (float)dtype};
-        int ts = ctx->table_cur;
-        if (!ctx->table_valid[ts] || std::memcmp(ctx->table_key[ts], key, sizeof key) != 0 ||
-            ctx->table_stream[ts] != stream) {
-            if (ctx->table_valid[ts]) {
-                if (ctx->table_stream[ts] == stream) {
-                    if (hipEventRecord(ctx->table_done[ts], stream) != hipSuccess) return L3_ERR_DEVICE;
-                    ctx->table_pending[ts] = true;
-                } else {
-                    if (hipDeviceSynchronize() != hipSuccess) return L3_ERR_DEVICE;
-                    for (int s = 0; s < kSlots; ++s) ctx->table_pending[s] = false;
-                }
+        uint16_t* build_into = nullptr;
+        hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream, &capture) != hipSuccess) return L3_ERR_DEVICE;
+        if (capture != hipStreamCaptureStatusNone) {
+            build_into = ctx->d_table_capture;
+        } else {
+            int ts = -1;
+            for (int k = 0; k < kSlots && ts < 0; ++k) {
+                const int cand = (ctx->table_cur + k) % kSlots;
+                if (ctx->table_valid[cand] && ctx->table_stream[cand] == stream &&
+                    std::memcmp(ctx->table_key[cand], key, sizeof key) == 0)
+                    ts = cand;
             }
-            ts = (ts + 1) % kSlots;
-            if (ctx->table_pending[ts]) {
-                if (hipEventSynchronize(ctx->table_done[ts]) != hipSuccess) return L3_ERR_DEVICE;
-                ctx->table_pending[ts] = false;
+            if (ts < 0) {
+                ts = (ctx->table_cur + 1) % kSlots;
+                if (ctx->table_valid[ts] && ctx->table_stream[ts] != stream && ctx->table_used_valid[ts] &&
+                    hipStreamWaitEvent(stream, ctx->table_used[ts], 0) != hipSuccess)
+                    return L3_ERR_DEVICE;
+                build_into = ctx->d_table[ts];
+                std::memcpy(ctx->table_key[ts], key, sizeof key);
+                ctx->table_valid[ts] = true;
+                ctx->table_stream[ts] = stream;
             }
-            hipLaunchKernelGGL(l3_build_table_kernel, dim3(3), dim3(256), 0, stream, mean[0], mean[1],
-                               mean[2], stdv[0], stdv[1], stdv[2], dtype, ctx->d_table[ts]);
-            std::memcpy(ctx->table_key[ts], key, sizeof key);
-            ctx->table_valid[ts] = true;
-            ctx->table_stream[ts] = stream;
             ctx->table_cur = ts;
+            table_slot = ts;
+            table = ctx->d_table[ts];
         }
-        table = ctx->d_table[ts];
+        if (build_into) {
+            hipLaunchKernelGGL(l3_build_table_kernel, dim3(3), dim3(256), 0, stream, mean[0], mean[1],
+                               mean[2], stdv[0], stdv[1], stdv[2], dtype, build_into);
+            table = build_into;
+        }
     }
     for (int k = 0; k < 3; ++k) {
         const int count = class_begin[k + 1] - class_begin[k];
@@ -960,6 +956,10 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         }
     }
     if (hipGetLastError() != hipSuccess) return L3_ERR_DEVICE;
+    if (table_slot >= 0) {
+        if (hipEventRecord(ctx->table_used[table_slot], stream) != hipSuccess) return L3_ERR_DEVICE;
+        ctx->table_used_valid[table_slot] = true;
+    }
     if (slot >= 0) {
         if (hipEventRecord(ctx->done[slot], stream) != hipSuccess) return L3_ERR_DEVICE;
         ctx->pending[slot] = true;
@@ -982,14 +982,26 @@ l3_status l3_ctx_create(l3_ctx** out, int device) {
     l3_ctx* ctx = new (std::nothrow) l3_ctx;
     if (!ctx) return L3_ERR_DEVICE;
     ctx->device = device;
-    for (int s = 0; s < kSlots; ++s) {
-        if (hipEventCreateWithFlags(&ctx->done[s], hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&ctx->table_done[s], hipEventDisableTiming) != hipSuccess ||
-            hipMalloc(reinterpret_cast<void**>(&ctx->d_table[s]), 768 * sizeof(uint16_t)) !=
-                hipSuccess) {
-            l3_ctx_destroy(ctx);
-            return L3_ERR_DEVICE;
-        }
+    {
+        /* L3_FLAT_ORDER=0 in the environment at creation keeps every image on the per-row order
+         * of work units (for comparisons; the flat order is never slower in measurements) */
+        const char* e = std::getenv("L3_FLAT_ORDER");
+        ctx->flat_order = !(e && e[0] == '0' && e[1] == 0);
+    }
+    /* host staging for up to three full argument blocks, so that batches of that size never
+     * make a call allocate */
+    ctx->scratch_cap = 3 * kArgDescs;
+    ctx->scratch = static_cast<L3ImageDesc*>(std::malloc((ctx->scratch_cap + kArgDescs) * sizeof(L3ImageDesc)));
+    bool ok = ctx->scratch &&
+              hipMalloc(reinterpret_cast<void**>(&ctx->d_table_capture), 768 * sizeof(uint16_t)) == hipSuccess;
+    for (int s = 0; s < kSlots && ok; ++s) {
+        ok = hipEventCreateWithFlags(&ctx->done[s], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&ctx->table_used[s], hipEventDisableTiming) == hipSuccess &&
+             hipMalloc(reinterpret_cast<void**>(&ctx->d_table[s]), 768 * sizeof(uint16_t)) == hipSuccess;
+    }
+    if (!ok) {
+        l3_ctx_destroy(ctx);
+        return L3_ERR_DEVICE;
     }
     *out = ctx;
     return L3_OK;
@@ -998,15 +1010,15 @@ l3_status l3_ctx_create(l3_ctx** out, int device) {
 void l3_ctx_destroy(l3_ctx* ctx) {
     if (!ctx) return;
     DeviceGuard guard(ctx->device);
-    /* kernels of the last fused calls may still read the current table */
-    if (ctx->table_valid[ctx->table_cur]) (void)hipDeviceSynchronize();
     for (int s = 0; s < kSlots; ++s) {
         if (ctx->pending[s]) (void)hipEventSynchronize(ctx->done[s]);
         if (ctx->done[s]) (void)hipEventDestroy(ctx->done[s]);
-        if (ctx->table_pending[s]) (void)hipEventSynchronize(ctx->table_done[s]);
-        if (ctx->table_done[s]) (void)hipEventDestroy(ctx->table_done[s]);
+        /* kernels of the last fused calls may still read the slot's table */
+        if (ctx->table_used_valid[s]) (void)hipEventSynchronize(ctx->table_used[s]);
+        if (ctx->table_used[s]) (void)hipEventDestroy(ctx->table_used[s]);
         if (ctx->d_table[s]) (void)hipFree(ctx->d_table[s]);
     }
+    if (ctx->d_table_capture) (void)hipFree(ctx->d_table_capture);
     release_slots(ctx);
     std::free(ctx->scratch);
     l3_encode_state_free(ctx->enc);

@@ -45,6 +45,19 @@ __device__ __forceinline__ uint32_t pk_mad_i16(uint32_t a, uint32_t b, uint32_t 
     return d;
 }
 
+/* Both 16-bit halves of v shifted right by the low half of `by`. */
+__device__ __forceinline__ uint32_t pk_lshr_b16_by_low(uint32_t by, uint32_t v) {
+    uint32_t d;
+    asm("v_pk_lshrrev_b16 %0, %1, %2 op_sel_hi:[0,1]" : "=v"(d) : "v"(by), "v"(v));
+    return d;
+}
+/* a * (low half of b) + c in both 16-bit halves, modulo 2^16. */
+__device__ __forceinline__ uint32_t pk_mad_u16_by_low(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t d;
+    asm("v_pk_mad_u16 %0, %1, %2, %3 op_sel_hi:[1,0,1]" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+
 /* Section 4.2, custom Paeth filter, on NP registers of two pixels at once (16-bit
  * fields holding 0..255).  Value-wise the nearest of TL, TR, T to TL + TR - T is:
  * with lo = min(TL,TR), hi = max(TL,TR), dl = T - lo, dh = hi - T (signed):

@@ -202,11 +202,8 @@ def test_seeded_random_shapes_one_call(l3, ctx, layout):
         assert np.array_equal(g, im), (k, im.shape, patches[k])
 
 
-@pytest.mark.parametrize("ppl", ["4", "8"])
-def test_both_lane_widths(l3, ctx, ppl, monkeypatch):
-    """The kernel exists with 4 and with 8 pixels per lane; the library picks one per
-    patch size.  Force each for every patch size, in all three output modes."""
-    monkeypatch.setenv("L3_PIXELS_PER_LANE", ppl)
+def test_all_patch_sizes_all_modes(l3, ctx):
+    """Every patch size of the GPU path in all three output modes on a mix of shapes."""
     images = [synth.cosine_field(900 + k, w, h) for k, (w, h) in
               enumerate([(450, 337), (129, 127), (33, 70), (1, 1), (260, 131)])]
     images.append(synth.uniform_bytes(950, 300, 200))
@@ -220,18 +217,20 @@ def test_both_lane_widths(l3, ctx, ppl, monkeypatch):
 
 
 @pytest.mark.parametrize("flat", ["1", "0"])
-def test_units_across_patch_rows(l3, ctx, flat, monkeypatch):
+def test_units_across_patch_rows(l3, flat, monkeypatch):
     """Shapes whose patch rows do not fill whole work units, so that the library numbers the
     units in flat order and a unit's patches lie in several patch rows (down to one patch per
     row); with and without a shorter last patch row; both layouts, padded rows.  The same
-    with the flat order switched off."""
+    with the flat order switched off (the switch is read when a context is created)."""
     monkeypatch.setenv("L3_FLAT_ORDER", flat)
+    ctx = l3.Context(0)
     shapes = [(40, 300), (32, 257), (70, 129), (33, 64), (450, 337), (97, 96), (200, 33), (130, 260),
               (1, 3000), (3, 1025)]
     images = [synth.cosine_field(1400 + k, w, h) for k, (w, h) in enumerate(shapes)]
     for patch in (32, 64, 128):
         for layout in ("hwc", "chw"):
             check_batch(l3, ctx, images, patch=patch, layout=layout, pad_cols=5)
+    ctx.close()
 
 
 def test_large_image_and_odd_output_address(l3, ctx):
@@ -491,6 +490,48 @@ def test_decode_batch_replayed_from_a_captured_graph(l3, ctx, count):
         assert (status.cpu().numpy() == 0).all()
         for t, w_ in zip(outs, want):
             assert np.array_equal(t.cpu().numpy(), w_)
+
+
+def test_fused_call_replayed_from_a_captured_graph(l3, ctx):
+    """Under stream capture the fused call records the build of its table into the graph (a
+    table of its own), so that replays stand alone: between the replays eager fused calls
+    with other constants run on the same context, and every replay must give the eager
+    result of its own constants."""
+    n = 12
+    shapes = synth.config2_shapes(n)
+    images = synth.config2(n)
+    crops = synth.config5_crops(shapes)
+    files = [oracle.encode(im) for im in images]
+    infos = [l3.peek_header(f) for f in files]
+    dfiles, keep = upload_files(files)
+    mean, stdv = (0.4, 0.5, 0.6), (0.2, 0.3, 0.4)
+    batch = l3.PreparedCropBatch(dfiles, infos, crops, mean, stdv)
+    out = torch.zeros((n, 3, 224, 224), dtype=torch.int16, device="cuda")
+    other = torch.zeros((n, 3, 224, 224), dtype=torch.int16, device="cuda")
+    status = torch.full((n,), 9, dtype=torch.int32, device="cuda")
+    want = np.stack([oracle.crop_normalize(im, x0, y0, flip, 224, 224, mean, stdv, 0)
+                     for im, (x0, y0, flip) in zip(images, crops)])
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        l3.decode_crop_normalize_batch_prepared(ctx, batch, 224, 224, out, status=status, stream=side)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), want)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        l3.decode_crop_normalize_batch_prepared(ctx, batch, 224, 224, out, status=status,
+                                                stream=torch.cuda.current_stream())
+    for rep in range(4):
+        out.fill_(rep + 1)
+        status.fill_(5)
+        # an eager call with other constants in between (five changes walk through every slot)
+        l3.decode_crop_normalize_batch(ctx, dfiles, infos, crops, 224, 224, (0.1 * rep, 0.2, 0.3),
+                                       (1.0, 0.5 + rep, 0.25), other)
+        torch.cuda.synchronize()
+        print(f"fused graph replay {rep}", flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (status.cpu().numpy() == 0).all()
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), want)
 
 
 def _decode_many_small(l3, ctx, images):
