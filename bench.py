@@ -10,9 +10,9 @@ default workload is the Cityscapes-shaped batch the headline metric is quoted on
 (32 images of 2048x1024, N = 128).  Several input/output buffer sets are rotated
 so that consecutive steps do not hit in the last-level cache.
 
-Prints one JSON line.  `roofline.achieved` is (file bytes read + decoded bytes
-written) per launch divided by the launch time measured with events on the
-launch stream; `cpu_baseline` is the CPU oracle decoding the same files on the
+Prints one JSON line.  `roofline` is the HBM view the target is stated in:
+(file bytes read + decoded bytes written) per launch divided by the launch time
+measured with events on the launch stream, against 8 TB/s; `cpu_baseline` is the CPU oracle decoding the same files on the
 host cores (a reported baseline, not a target).
 """
 import argparse
@@ -28,15 +28,27 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: plain (non-packed-rate) vector ALU lane-operations
-VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# VALU instructions of the steady-state row per lane (51) over the 4 bytes the lane decodes
-ALGORITHMIC_LANE_OPS_PER_DECODED_BYTE = 51 / 4
+VALU_ISSUE_PER_S = 256 * 4 * 2.4e9 / 4      # wave instructions per second: 1024 SIMDs, one per 4 cycles
+KERNEL_SOURCES = ("paper_2208_08711_amd/csrc/l3_device.hip", "paper_2208_08711_amd/csrc/l3_gfx950.h")
 
 
-def read_traffic(workload):
-    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "l3_decode_kernel_%s_traffic.txt" % workload)
+def kernel_source_stamp():
+    """Hash of the decode kernel's sources: counter summaries under profiles/ carry the stamp of
+    the sources they were measured with, and count only while it still matches."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def read_counters(workload):
+    """Per-launch counters of the decode kernel from the committed rocprofv3 summary of this
+    workload (profiles/l3_decode_kernel_<workload>_counters.txt, written by the profile run):
+    HBM bytes (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy) and SQ_INSTS_VALU.  None if there
+    is no summary or if it was measured with other kernel sources than the ones in the tree."""
+    path = os.path.join(ROOT, "profiles", "l3_decode_kernel_%s_counters.txt" % workload)
     if not os.path.exists(path):
         return None
     vals = {}
@@ -45,10 +57,10 @@ def read_traffic(workload):
             line = line.split("#", 1)[0].strip()
             if "=" in line:
                 k, v = line.split("=", 1)
-                vals[k.strip()] = int(v)
-    if "fetch_bytes_per_launch" in vals and "write_bytes_per_launch" in vals:
-        return vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"]
-    return None
+                vals[k.strip()] = v.strip()
+    if vals.get("kernel_source_stamp") != kernel_source_stamp():
+        return None
+    return vals
 
 
 def make_workload(name, batch=0):
@@ -57,6 +69,11 @@ def make_workload(name, batch=0):
         n = batch or 32
         return synth.config3(n), ("Cityscapes-shaped: %d RGB images 2048x1024, Voronoi regions + texture, "
                                   "N=128" % n)
+    if name == "cityscapes044":
+        n = batch or 32
+        return [synth.cosine_field(3500 + k, 2048, 1024, sigma=0.93) for k in range(n)], (
+            "Cityscapes-sized at the paper's compression ratio: %d RGB images 2048x1024, smooth cosine "
+            "field + noise sigma 0.93 (compressed/raw 0.44 as in the paper's Table compratio), N=128" % n)
     if name == "fhd":
         n = batch or 32
         return synth.config3(n, width=1920, height=1080), ("FHD: %d RGB images 1920x1080, Voronoi regions + "
@@ -316,7 +333,8 @@ def main():
     ap.add_argument("--steps", type=int, default=3000)
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="cityscapes",
-                    help="cityscapes (default, the configuration the metric is quoted on), fhd, kitti, "
+                    help="cityscapes (default, the configuration the metric is quoted on), cityscapes044 "
+                         "(same shape, content at the paper's Cityscapes compression ratio), fhd, kitti, "
                          "imagenet, uhd, train224")
     ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -361,7 +379,9 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU (there is no CPU fallback)")
 
-    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+    # one thread per host core, but never more than the 16 a one-GPU machine grants its jobs
+    host_cores = os.cpu_count() or 1
+    cores = min(host_cores, 16)
     images, label = make_workload(args.workload, args.batch)
     with ThreadPoolExecutor(cores) as pool:
         files = list(pool.map(lambda im: l3.encode_cpu(im, args.patch), images))
@@ -499,9 +519,20 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     launch_ms = gpu_ms / args.steps
     algo_bytes = file_bytes + decoded_bytes
-    algo_lane_ops = (fused_decoded if fused else decoded_bytes) * ALGORITHMIC_LANE_OPS_PER_DECODED_BYTE
     patch = int(infos[0].patch)
-    traffic = read_traffic(args.workload)
+    counters = read_counters(args.workload)
+    traffic, valu = None, None
+    if counters:
+        if "fetch_bytes_per_launch" in counters and "write_bytes_per_launch" in counters:
+            traffic = int(counters["fetch_bytes_per_launch"]) + int(counters["write_bytes_per_launch"])
+        if "sq_insts_valu_per_launch" in counters:
+            insts = float(counters["sq_insts_valu_per_launch"])
+            # measured wave instructions of the vector ALU against what 1024 SIMDs can issue
+            # during one launch at the nominal 2.4 GHz (one instruction per SIMD per 4 cycles)
+            valu = {"sq_insts_valu_per_launch": insts,
+                    "issue_fraction_at_2.4GHz": insts / (VALU_ISSUE_PER_S * launch_ms * 1e-3),
+                    "insts_per_256_decoded_bytes": insts / ((fused_decoded if fused else decoded_bytes) / 256.0),
+                    "kernel_source_stamp": counters.get("kernel_source_stamp")}
     result = {
         "metric": "decoded images/s",
         "value": n / (ms_per_step * 1e-3),
@@ -522,24 +553,23 @@ def main():
                    "compressed_over_raw": compressed_over_raw},
         "decoded_GBps": decoded_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_fraction": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        # the kernel is bound by plain vector-ALU issue (measured VALU busy ~85 %); the HBM
-        # view, which the target is stated in, is given beside it
-        "roofline": {"bound": "alu",
-                     "achieved": algo_lane_ops / (launch_ms * 1e-3) / 1e12,
-                     "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
-                     "frac": algo_lane_ops / (launch_ms * 1e-3) / 1e12 / VALU_PEAK_TLANEOPS,
+        # The fraction the target is stated in: algorithmic bytes (files read + output written)
+        # per launch over the launch time (events on the launch stream) over 8 TB/s.  `traffic`
+        # and `valu` come from the committed rocprofv3 counter summary of this workload and are
+        # null when the kernel sources have changed since it was taken.
+        "roofline": {"bound": "hbm",
+                     "achieved": algo_bytes / (launch_ms * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": algo_bytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                      "traffic": traffic,
                      "kernel": ("l3_decode_kernel_args<%d, 4, %s, %d>" % (
                                     patch, "TENSOR" if fused else args.layout.upper(), 32 if n <= 32 else 256)
                                 if n <= 256 else
                                 "l3_decode_kernel<%d, 4, %s>" % (patch, "TENSOR" if fused else args.layout.upper())),
                      "launch_ms": launch_ms,
-                     "algorithmic_lane_ops_per_decoded_byte": ALGORITHMIC_LANE_OPS_PER_DECODED_BYTE,
-                     "hbm": {"achieved": algo_bytes / (launch_ms * 1e-3) / 1e9,
-                             "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                             "frac": algo_bytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                             "algorithmic_bytes_per_launch": algo_bytes,
-                             "device_copy_GBps": copy_gbps}},
+                     "algorithmic_bytes_per_launch": algo_bytes,
+                     "device_copy_GBps": copy_gbps,
+                     "valu": valu},
     }
 
     if args.overlap_gemm:
@@ -569,7 +599,8 @@ def main():
                 list(pool.map(oracle.decode, sample))
                 many = min(many, time.perf_counter() - t)
         result["cpu_baseline"] = {
-            "value": len(sample) / many, "unit": "images/s", "cores": cores, "kind": "oracle",
+            "value": len(sample) / many, "unit": "images/s", "cores": cores, "host_cpu_count": host_cores,
+            "kind": "oracle",
             "sample": f"{len(sample)} images of the same batch, best of three passes over {cores} "
                       f"threads (one image per task); single thread over {len(single)} images: "
                       f"{1.0 / one:.2f} images/s",
