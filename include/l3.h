@@ -51,7 +51,8 @@ typedef enum {
     L3_ERR_CORRUPT = 4,          /* header fields or offsets inconsistent */
     L3_ERR_BUFFER_TOO_SMALL = 5, /* output capacity insufficient */
     L3_ERR_UNSUPPORTED = 6,      /* valid file, but not handled by the GPU path */
-    L3_ERR_DEVICE = 7            /* a HIP runtime call failed / no usable GPU */
+    L3_ERR_DEVICE = 7,           /* a HIP runtime call failed / no usable GPU */
+    L3_ERR_LIMIT = 8             /* the request exceeds a fixed limit of the entry point */
 } l3_status;
 
 /* Static, NUL-terminated description of a status value.  Never NULL. */
@@ -183,6 +184,24 @@ l3_status l3_decode_crop_normalize_batch(l3_ctx* ctx, const l3_item* items,
                                          const float mean[3], const float stdv[3],
                                          l3_dtype dtype, void* d_out_nchw,
                                          uint32_t* d_status, void* stream);
+
+/* For callers that cannot allocate device memory while they run (work recorded under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same call as
+ * l3_decode_crop_normalize_batch, with the same arguments, results and errors, that
+ * allocates nothing, on the host or on the device.  Its table of normalised values lives in
+ * a static device array of the library (1536 bytes per GPU, held until the process ends),
+ * which is rebuilt on `stream` by every call; descriptors travel in the kernel arguments.
+ * At most L3_NOALLOC_MAX_IMAGES images per call: more give L3_ERR_LIMIT and enqueue
+ * nothing (so does an image with more work units than one launch holds).
+ * All calls on one GPU, from any context, share that one table: calls that may overlap on
+ * the device (different streams) race on it unless they use the same constants. */
+#define L3_NOALLOC_MAX_IMAGES 256
+l3_status l3_decode_crop_normalize_batch_noalloc(l3_ctx* ctx, const l3_item* items,
+                                                 const l3_crop* crops, int n,
+                                                 uint32_t crop_w, uint32_t crop_h,
+                                                 const float mean[3], const float stdv[3],
+                                                 l3_dtype dtype, void* d_out_nchw,
+                                                 uint32_t* d_status, void* stream);
 
 typedef struct {
     const uint8_t* d_rgb;      /* DEVICE: interleaved 8-bit RGB, rows row_stride bytes apart */

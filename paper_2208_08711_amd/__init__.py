@@ -7,6 +7,6 @@ from .binding import (  # noqa: F401
     L3Error, Context, Info, default_patch, encode_bound, encode_cpu, peek_header,
     decode_batch, decode_crop_normalize_batch, PreparedBatch, decode_batch_prepared,
     PreparedCropBatch, decode_crop_normalize_batch_prepared, encode_batch, library_path, status_string,
-    LAYOUT_HWC, LAYOUT_CHW, BF16, FP16, EXPORTED_SYMBOLS,
+    LAYOUT_HWC, LAYOUT_CHW, BF16, FP16, EXPORTED_SYMBOLS, NOALLOC_MAX_IMAGES,
     ablation_decode_batch, ABLATION_PIXEL_BD, ABLATION_CUSTOM_FILTER, ABLATION_SERIAL_PATCHES, ABLATION_DIAGONAL,
 )

@@ -19,7 +19,7 @@ BF16, FP16 = 0, 1
 EXPORTED_SYMBOLS = (
     "l3_status_string", "l3_default_patch", "l3_encode_bound", "l3_encode_cpu", "l3_peek_header",
     "l3_ctx_create", "l3_ctx_destroy", "l3_decode_batch", "l3_decode_crop_normalize_batch",
-    "l3_encode_batch", "l3_ablation_encode_cpu", "l3_ablation_decode_batch",
+    "l3_decode_crop_normalize_batch_noalloc", "l3_encode_batch", "l3_ablation_encode_cpu", "l3_ablation_decode_batch",
 )
 
 
@@ -99,6 +99,8 @@ def _load():
         ctypes.c_uint32, ctypes.c_uint32, ctypes.POINTER(ctypes.c_float),
         ctypes.POINTER(ctypes.c_float), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_void_p]
+    lib.l3_decode_crop_normalize_batch_noalloc.restype = ctypes.c_int
+    lib.l3_decode_crop_normalize_batch_noalloc.argtypes = lib.l3_decode_crop_normalize_batch.argtypes
     lib.l3_encode_batch.restype = ctypes.c_int
     lib.l3_encode_batch.argtypes = [ctypes.c_void_p, ctypes.POINTER(_EncodeItem), ctypes.c_int,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -246,9 +248,13 @@ def decode_batch_prepared(ctx, batch, status=None, stream=None):
                                    _stream_ptr(stream)), "l3_decode_batch")
 
 
+NOALLOC_MAX_IMAGES = 256
+
+
 def decode_crop_normalize_batch(ctx, files, infos, crops, crop_w, crop_h, mean, stdv, out,
-                                dtype=BF16, status=None, stream=None):
-    """crops: list of (x0, y0, flip); out: 16-bit device tensor [n, 3, crop_h, crop_w]."""
+                                dtype=BF16, status=None, stream=None, noalloc=False):
+    """crops: list of (x0, y0, flip); out: 16-bit device tensor [n, 3, crop_h, crop_w].
+    noalloc=True calls l3_decode_crop_normalize_batch_noalloc with the same arguments."""
     n = len(files)
     arr = _items(files, infos, None, None)
     cr = (_Crop * max(n, 1))()
@@ -256,10 +262,12 @@ def decode_crop_normalize_batch(ctx, files, infos, crops, crop_w, crop_h, mean, 
         cr[i].x0, cr[i].y0, cr[i].flip = int(x0), int(y0), int(bool(flip))
     m = (ctypes.c_float * 3)(*mean)
     s = (ctypes.c_float * 3)(*stdv)
-    _check(_load().l3_decode_crop_normalize_batch(
+    lib = _load()
+    call = lib.l3_decode_crop_normalize_batch_noalloc if noalloc else lib.l3_decode_crop_normalize_batch
+    _check(call(
         ctx.handle, arr, cr, n, crop_w, crop_h, m, s, dtype, ctypes.c_void_p(out.data_ptr()),
         ctypes.c_void_p(status.data_ptr() if status is not None else None), _stream_ptr(stream)),
-        "l3_decode_crop_normalize_batch")
+        "l3_decode_crop_normalize_batch_noalloc" if noalloc else "l3_decode_crop_normalize_batch")
 
 
 class PreparedCropBatch:

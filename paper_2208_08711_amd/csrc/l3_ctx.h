@@ -36,6 +36,7 @@ struct l3_ctx {
     hipEvent_t table_used[kSlots] = {};
     bool table_used_valid[kSlots] = {};
     int table_cur = 0;                    /* the slot the last fused call used */
+    uint16_t* static_table = nullptr;     /* device: this GPU's copy of the library's static table */
     hipEvent_t done[kSlots] = {};         /* the slot's kernels have finished */
     bool pending[kSlots] = {};
     int next = 0;

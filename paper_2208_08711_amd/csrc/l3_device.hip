@@ -43,6 +43,7 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "l3_internal.h"
@@ -653,7 +654,31 @@ __global__ void l3_prepare_kernel(const uint64_t* __restrict__ pinned_src, uint6
     if (status && i < n_status) status[i] = 0;
 }
 
+/* The table of normalised values of l3_decode_crop_normalize_batch_noalloc: memory that exists
+ * from the moment the library is loaded, one copy per GPU, so that the call itself allocates
+ * nothing.  Host code never uses this name as an address: l3_ctx_create asks the runtime for the
+ * address of the current device's copy once and keeps it (static_table_of). */
+constexpr int kStaticTableEntries = 768;
+static __device__ __align__(256) uint16_t scratch[kStaticTableEntries];
+
 /* ---- host side: context, planning, launch ------------------------------- */
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_table_mutex;
+uint16_t* g_static_table[kMaxDevices] = {};
+
+/* Address of the current device's copy of `scratch`; asked for once per device, with that
+ * device current.  NULL if the runtime refuses. */
+uint16_t* static_table_of(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_static_table_mutex);
+    if (!g_static_table[device]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        g_static_table[device] = static_cast<uint16_t*>(ptr);
+    }
+    return g_static_table[device];
+}
 
 
 typedef void (*decode_kernel_t)(const L3ImageDesc*, uint32_t, uint32_t, uint32_t*, uint32_t, uint32_t,
@@ -766,7 +791,8 @@ l3_status check_item(const l3_item& it, L3ImageDesc* d) {
 
 l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int n, int mode,
                     uint32_t crop_w, uint32_t crop_h, const float* mean, const float* stdv,
-                    int dtype, void* d_out_tensor, uint32_t* d_status, void* stream_v) {
+                    int dtype, void* d_out_tensor, uint32_t* d_status, void* stream_v,
+                    bool no_alloc = false) {
     if (!ctx || n < 0 || (n > 0 && !items)) return L3_ERR_INVALID_ARG;
     if (n == 0) return L3_OK;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
@@ -774,6 +800,7 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return L3_ERR_DEVICE;
     l3_status st = L3_OK;
+    if (no_alloc && (size_t)n > ctx->scratch_cap) return L3_ERR_LIMIT;   /* cannot happen: n <= 256 */
     if ((size_t)n > ctx->scratch_cap) {
         size_t cap = 256;
         while (cap < (size_t)n) cap *= 2;
@@ -849,6 +876,7 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         if (count > (uint64_t)kArgDescs || count * max_units[k] > 0x7FFFFF00ull) in_args = false;
     }
 
+    if (no_alloc && !in_args) return L3_ERR_LIMIT;
     int slot = -1;
     L3ImageDesc* d_descs = nullptr;
     if (!in_args) {
@@ -878,6 +906,7 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
     if (mode == L3_MODE_TENSOR) {
         /* The table of the 256 normalised values per channel, built by a small kernel on the
          * call's stream ahead of the kernel that reads it.
+         *  - no_alloc: always built, into the library's static table of this GPU.
          *  - under stream capture: always built, into a table of its own, so that the graph
          *    holds the build and replays stand alone.
          *  - otherwise cached: a slot per (constants, stream) pair; a call that finds its pair
@@ -888,7 +917,9 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         uint16_t* build_into = nullptr;
         hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
         if (hipStreamIsCapturing(stream, &capture) != hipSuccess) return L3_ERR_DEVICE;
-        if (capture != hipStreamCaptureStatusNone) {
+        if (no_alloc) {
+            build_into = ctx->static_table;
+        } else if (capture != hipStreamCaptureStatusNone) {
             build_into = ctx->d_table_capture;
         } else {
             int ts = -1;
@@ -988,11 +1019,12 @@ l3_status l3_ctx_create(l3_ctx** out, int device) {
         const char* e = std::getenv("L3_FLAT_ORDER");
         ctx->flat_order = !(e && e[0] == '0' && e[1] == 0);
     }
+    ctx->static_table = static_table_of(device);
     /* host staging for up to three full argument blocks, so that batches of that size never
      * make a call allocate */
     ctx->scratch_cap = 3 * kArgDescs;
     ctx->scratch = static_cast<L3ImageDesc*>(std::malloc((ctx->scratch_cap + kArgDescs) * sizeof(L3ImageDesc)));
-    bool ok = ctx->scratch &&
+    bool ok = ctx->static_table && ctx->scratch &&
               hipMalloc(reinterpret_cast<void**>(&ctx->d_table_capture), 768 * sizeof(uint16_t)) == hipSuccess;
     for (int s = 0; s < kSlots && ok; ++s) {
         ok = hipEventCreateWithFlags(&ctx->done[s], hipEventDisableTiming) == hipSuccess &&
@@ -1043,6 +1075,20 @@ l3_status l3_decode_crop_normalize_batch(l3_ctx* ctx, const l3_item* items, cons
     if (n > 0 && (stdv[0] == 0.0f || stdv[1] == 0.0f || stdv[2] == 0.0f)) return L3_ERR_INVALID_ARG;
     return run_batch(ctx, items, crops, n, L3_MODE_TENSOR, crop_w, crop_h, mean, stdv, (int)dtype,
                      d_out_nchw, d_status, stream);
+}
+
+l3_status l3_decode_crop_normalize_batch_noalloc(l3_ctx* ctx, const l3_item* items,
+                                                 const l3_crop* crops, int n, uint32_t crop_w,
+                                                 uint32_t crop_h, const float mean[3],
+                                                 const float stdv[3], l3_dtype dtype,
+                                                 void* d_out_nchw, uint32_t* d_status, void* stream) {
+    if (n > L3_NOALLOC_MAX_IMAGES) return L3_ERR_LIMIT;
+    if (n > 0 && (!crops || !mean || !stdv || !d_out_nchw || crop_w == 0 || crop_h == 0))
+        return L3_ERR_INVALID_ARG;
+    if (dtype != L3_BF16 && dtype != L3_FP16) return L3_ERR_INVALID_ARG;
+    if (n > 0 && (stdv[0] == 0.0f || stdv[1] == 0.0f || stdv[2] == 0.0f)) return L3_ERR_INVALID_ARG;
+    return run_batch(ctx, items, crops, n, L3_MODE_TENSOR, crop_w, crop_h, mean, stdv, (int)dtype,
+                     d_out_nchw, d_status, stream, true);
 }
 
 }  // extern "C"

@@ -126,6 +126,7 @@ const char* l3_status_string(l3_status s) {
         case L3_ERR_BUFFER_TOO_SMALL: return "output buffer too small";
         case L3_ERR_UNSUPPORTED: return "not supported by this build";
         case L3_ERR_DEVICE: return "HIP runtime error or no usable GPU";
+        case L3_ERR_LIMIT: return "request exceeds a fixed limit of the entry point";
     }
     return "unknown status";
 }

@@ -33,8 +33,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    seen = {l3.status_string(k) for k in range(8)}
-    assert len(seen) == 8 and "unknown status" not in seen
+    seen = {l3.status_string(k) for k in range(9)}
+    assert len(seen) == 9 and "unknown status" not in seen
     assert l3.status_string(99) == "unknown status"
 
 
