@@ -283,8 +283,11 @@ def measure_encode(torch, l3, ctx, images, files, stream, patch):
 
 
 def measure_overlap(torch, step, stream, steps, decode_alone_ms):
-    """Decode steps on `stream`, a bf16 GEMM loop on a second stream (both default
-    priority): each alone and both together."""
+    """Decode steps on `stream`, a bf16 GEMM loop on a second stream (both default priority):
+    each alone, and the rates of both while both streams have work.  The decode steps are
+    enqueued in chunks with an event behind each; the chunks that lie entirely inside the GEMM
+    loop's interval give the decode rate beside compute, the interval itself the GEMM rate
+    beside decoding (the decode stream is given enough steps to outlast the loop)."""
     side = torch.cuda.Stream()
     m = 8192
     a = torch.randn((m, m), dtype=torch.bfloat16, device="cuda")
@@ -296,34 +299,40 @@ def measure_overlap(torch, step, stream, steps, decode_alone_ms):
             for _ in range(k):
                 torch.matmul(a, b, out=out)
 
-    gemms(5)
+    gemms(60)                    # long enough for the clocks to settle under this load too
     torch.cuda.synchronize()
     g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     g0.record(side)
-    gemms(20)
+    gemms(60)
     g1.record(side)
     torch.cuda.synchronize()
-    gemm_alone_ms = g0.elapsed_time(g1) / 20
-    # together: enough GEMMs to cover the decode steps
-    n_gemm = max(4, int(steps * decode_alone_ms / gemm_alone_ms) + 2)
-    d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    gemm_alone_ms = g0.elapsed_time(g1) / 60
+    n_gemm, chunk = 150, 5
+    # decode steps: several times what fits beside the loop even if decoding kept its full speed
+    n_chunks = max(40, int(1.5 * n_gemm * gemm_alone_ms / (decode_alone_ms * chunk)) // 8)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_chunks + 1)]
     g0.record(side)
-    d0.record(stream)
-    done_g = 0
-    for k in range(steps):
-        step(k)
-        want = (k + 1) * n_gemm // steps
-        if want > done_g:
-            gemms(want - done_g)
-            done_g = want
-    d1.record(stream)
+    gemms(n_gemm)
     g1.record(side)
+    marks[0].record(stream)
+    for c in range(n_chunks):
+        for k in range(chunk):
+            step(c * chunk + k)
+        marks[c + 1].record(stream)
     torch.cuda.synchronize()
+    gemm_span = g0.elapsed_time(g1)
+    inside = [marks[c].elapsed_time(marks[c + 1]) / chunk for c in range(n_chunks)
+              if g0.elapsed_time(marks[c]) >= 0.0 and g0.elapsed_time(marks[c + 1]) <= gemm_span]
+    outlasted = g0.elapsed_time(marks[n_chunks]) > gemm_span
+    beside = sum(inside) / len(inside) if inside else None
     return {"compute": "torch.matmul bf16 %dx%dx%d on a second stream, default priority" % (m, m, m),
+            "gemms": n_gemm, "decode_steps_enqueued": n_chunks * chunk,
+            "decode_steps_inside_the_gemm_loop": len(inside) * chunk,
+            "decode_stream_outlasted_the_gemm_loop": outlasted,
             "decode_ms_per_step_alone": decode_alone_ms,
-            "decode_ms_per_step_beside_compute": d0.elapsed_time(d1) / steps,
+            "decode_ms_per_step_beside_compute": beside,
             "gemm_ms_alone": gemm_alone_ms,
-            "gemm_ms_beside_decode": g0.elapsed_time(g1) / n_gemm,
+            "gemm_ms_beside_decode": gemm_span / n_gemm,
             "gemm_TFLOPs_alone": 2.0 * m ** 3 / (gemm_alone_ms * 1e-3) / 1e12}
 
 
