@@ -169,14 +169,11 @@ typedef enum { L3_BF16 = 0, L3_FP16 = 1 } l3_dtype;
  * items[i].d_out / out_row_stride are ignored.  crops is a HOST array of n
  * entries; every window must lie inside its image.  mean and stdv are HOST
  * arrays of 3 floats (stdv non-zero).  Other arguments as l3_decode_batch.
- * The context keeps device tables of the 256 values of y per channel, one per pair of
- * constants (mean, stdv, dtype) and stream in use, at most four: a call that finds its
- * pair builds nothing and waits for nothing; a new pair builds its table on the call's
- * stream and, where it takes over the table of a pair last used on another stream, makes
- * its stream wait on the device for the kernels that still read it (the host never
- * waits).  Under stream capture the table is built inside the captured work, into a table
- * of its own, so that a replayed graph stands alone; captured fused calls of one context
- * share that table and must not run concurrently with different constants.
+ * The 768 possible values of y (l3_normalized_values) travel inside the arguments of the
+ * call's kernels: no table in device memory, nothing built ahead of the decode kernel, the
+ * same work recorded under stream capture as outside it, and calls with different constants
+ * may run at the same time on different streams.  (The context remembers the values of the
+ * last call's constants in host memory.)
  * Errors: as l3_decode_batch, plus INVALID_ARG for a window outside its image. */
 l3_status l3_decode_crop_normalize_batch(l3_ctx* ctx, const l3_item* items,
                                          const l3_crop* crops, int n,
@@ -184,6 +181,14 @@ l3_status l3_decode_crop_normalize_batch(l3_ctx* ctx, const l3_item* items,
                                          const float mean[3], const float stdv[3],
                                          l3_dtype dtype, void* d_out_nchw,
                                          uint32_t* d_status, void* stream);
+
+/* The values the fused call can write, as 16-bit patterns: out[c*256 + v] holds
+ * y = (v/255 - mean[c]) / stdv[c] for byte value v of channel c, worked out as stated above
+ * (IEEE binary32: divide, subtract, divide, each rounded, nothing fused; then rounded to
+ * nearest-even to dtype).  Host only; all pointers HOST.  Errors: INVALID_ARG (NULL pointer,
+ * unknown dtype). */
+l3_status l3_normalized_values(const float mean[3], const float stdv[3], l3_dtype dtype,
+                               uint16_t out[768]);
 
 /* For callers that cannot allocate device memory while they run (work recorded under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same call as

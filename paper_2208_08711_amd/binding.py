@@ -18,6 +18,7 @@ BF16, FP16 = 0, 1
 
 EXPORTED_SYMBOLS = (
     "l3_status_string", "l3_default_patch", "l3_encode_bound", "l3_encode_cpu", "l3_peek_header",
+    "l3_normalized_values",
     "l3_ctx_create", "l3_ctx_destroy", "l3_decode_batch", "l3_decode_crop_normalize_batch",
     "l3_decode_crop_normalize_batch_noalloc", "l3_encode_batch", "l3_ablation_encode_cpu", "l3_ablation_decode_batch",
 )
@@ -86,6 +87,9 @@ def _load():
                                              ctypes.c_int, ctypes.c_void_p]
     lib.l3_peek_header.restype = ctypes.c_int
     lib.l3_peek_header.argtypes = [u8p, ctypes.c_size_t, ctypes.POINTER(Info)]
+    lib.l3_normalized_values.restype = ctypes.c_int
+    lib.l3_normalized_values.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float),
+                                         ctypes.c_int, ctypes.POINTER(ctypes.c_uint16)]
     lib.l3_ctx_create.restype = ctypes.c_int
     lib.l3_ctx_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
     lib.l3_ctx_destroy.restype = None
@@ -158,6 +162,17 @@ def peek_header(file):
     info = Info()
     _check(_load().l3_peek_header(_u8(a), a.size, ctypes.byref(info)), "l3_peek_header")
     return info
+
+
+def normalized_values(mean, stdv, dtype=0):
+    """l3_normalized_values: uint16 numpy array [3, 256] of the bit patterns the fused call
+    writes for every byte value of every channel (dtype: BF16 = 0 or FP16 = 1)."""
+    m = (ctypes.c_float * 3)(*mean)
+    s = (ctypes.c_float * 3)(*stdv)
+    out = np.empty((3, 256), dtype=np.uint16)
+    _check(_load().l3_normalized_values(m, s, int(dtype), out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16))),
+           "l3_normalized_values")
+    return out
 
 
 class Context:

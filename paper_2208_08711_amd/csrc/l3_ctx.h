@@ -25,17 +25,11 @@ struct l3_ctx {
     L3ImageDesc* h_stage[kSlots] = {};    /* pinned host */
     L3ImageDesc* d_descs[kSlots] = {};    /* device */
     bool flat_order = true;               /* flat order of work units allowed (L3_FLAT_ORDER=0 at creation: off) */
-    /* Fused path: tables of the 256 normalised values per channel, one slot per (constants,
-     * stream) pair in use; table_used[s] is recorded behind every call that reads slot s, so
-     * that a call on another stream that takes the slot over can wait for it on the device. */
-    uint16_t* d_table[kSlots] = {};       /* device: 768 entries each */
-    uint16_t* d_table_capture = nullptr;  /* device: the table of calls made under stream capture */
-    float table_key[kSlots][7] = {};      /* mean, stdv, dtype the slot's table was built with */
-    bool table_valid[kSlots] = {};
-    hipStream_t table_stream[kSlots] = {};
-    hipEvent_t table_used[kSlots] = {};
-    bool table_used_valid[kSlots] = {};
-    int table_cur = 0;                    /* the slot the last fused call used */
+    /* Fused path: the table of normalised values of the last call's constants (host memory;
+     * it travels in the kernel arguments) */
+    uint16_t table_bits[768] = {};
+    float table_key[7] = {};              /* mean, stdv, dtype it was worked out for */
+    bool table_valid = false;
     uint16_t* static_table = nullptr;     /* device: this GPU's copy of the library's static table */
     hipEvent_t done[kSlots] = {};         /* the slot's kernels have finished */
     bool pending[kSlots] = {};

@@ -117,6 +117,32 @@ __device__ __forceinline__ uint32_t load_u32_any_alignment(const uint8_t* p) {
     return *reinterpret_cast<global_const_u32_any*>((uintptr_t)p);
 }
 
+/* ---- the fused epilogue's table ------------------------------------------- */
+
+/* The 256 normalised values per channel as 16-bit patterns, [channel][byte value]: what
+ * the fused kernels look pixels up in.  It travels inside the kernel arguments. */
+struct L3Table {
+    uint16_t bits[768];
+};
+struct L3NoTable {};
+template <int MODE> struct TailFor { typedef L3NoTable type; };
+template <> struct TailFor<L3_MODE_TENSOR> { typedef L3Table type; };
+
+/* y = (v/255 - mean) / stdv in IEEE binary32 without contraction, rounded to nearest-even
+ * to the 16-bit type; returns its bits.  (The host works the same values out in
+ * l3_normalized_values; the call that keeps its table in device memory uses this one.) */
+__device__ __forceinline__ uint16_t normalised_bits(uint32_t v, float mean, float stdv, int dtype) {
+    const float y = __fdiv_rn(__fsub_rn(__fdiv_rn((float)v, 255.0f), mean), stdv);
+    if (dtype == L3_BF16) {
+        uint32_t u = __float_as_uint(y);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        return (uint16_t)(u >> 16);
+    }
+    const _Float16 h = (_Float16)y;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
 /* ---- the decode kernel ---------------------------------------------------- */
 
 template <int N, int PPL, int MODE>
@@ -370,15 +396,17 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                 if (row >= 0 && row < (int32_t)crop_h && nvalid) {
                     const int32_t col0 = (int32_t)x - win_x0;   /* window column of pixel 0 */
                     const bool whole = nvalid == 4 && col0 >= 0 && col0 + 4 <= (int32_t)crop_w;
-                    /* all twelve table reads first, so that they travel together */
-                    uint32_t e[3][4];
+                    /* all twelve table reads first, so that they travel together; each lands
+                     * in the half of the register it is stored from (elements 0|1 and 2|3 of
+                     * the word), so nothing has to be packed afterwards */
+                    u16x2 q[3][2];
 #pragma unroll
                     for (int ch = 0; ch < 3; ++ch) {
                         const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
-                        e[ch][0] = s_lut[ch * 256 + (word & 0xFFu)];
-                        e[ch][1] = s_lut[ch * 256 + ((word >> 8) & 0xFFu)];
-                        e[ch][2] = s_lut[ch * 256 + ((word >> 16) & 0xFFu)];
-                        e[ch][3] = s_lut[ch * 256 + (word >> 24)];
+                        q[ch][0].x = s_lut[ch * 256 + (word & 0xFFu)];
+                        q[ch][0].y = s_lut[ch * 256 + ((word >> 8) & 0xFFu)];
+                        q[ch][1].x = s_lut[ch * 256 + ((word >> 16) & 0xFFu)];
+                        q[ch][1].y = s_lut[ch * 256 + (word >> 24)];
                     }
                     /* element (ch, row, 0) of this image; planes are crop_h * crop_w apart */
                     global_u16* line = reinterpret_cast<global_u16*>((uintptr_t)out_base) + (size_t)row * crop_w;
@@ -388,13 +416,15 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                         asm volatile("" : "+v"(col));      /* stays the store's 32-bit offset */
 #pragma unroll
                         for (int ch = 0; ch < 3; ++ch) {
+                            const uint32_t e01 = __builtin_bit_cast(uint32_t, q[ch][0]);
+                            const uint32_t e23 = __builtin_bit_cast(uint32_t, q[ch][1]);
                             u32x2 v;
-                            if (win_flip) {
-                                v.x = e[ch][3] | (e[ch][2] << 16);
-                                v.y = e[ch][1] | (e[ch][0] << 16);
+                            if (win_flip) {               /* the same for the whole image: 3 2 | 1 0 */
+                                v.x = __builtin_amdgcn_alignbit(e23, e23, 16);
+                                v.y = __builtin_amdgcn_alignbit(e01, e01, 16);
                             } else {
-                                v.x = e[ch][0] | (e[ch][1] << 16);
-                                v.y = e[ch][2] | (e[ch][3] << 16);
+                                v.x = e01;
+                                v.y = e23;
                             }
                             __builtin_nontemporal_store(
                                 v, reinterpret_cast<global_u32x2_any*>(line + ch * plane + col));
@@ -408,7 +438,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                                 int32_t col = col0 + k;
                                 if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
                                     if (win_flip) col = (int32_t)crop_w - 1 - col;
-                                    out16[col] = (uint16_t)e[ch][k];
+                                    out16[col] = (k & 1) ? q[ch][k / 2].y : q[ch][k / 2].x;
                                 }
                             }
                         }
@@ -585,15 +615,24 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     if (flags && active && status) atomicOr(&status[d.status_index], flags);
 }
 
+/* Where a fused kernel reads its table: in device memory if the call gave one, else in its
+ * own arguments (the argument segment is ordinary device memory). */
+template <int MODE>
+__device__ __forceinline__ const uint16_t* table_of(const uint16_t* lut, const L3NoTable&) { return lut; }
+template <int MODE>
+__device__ __forceinline__ const uint16_t* table_of(const uint16_t* lut, const L3Table& tail) {
+    return lut ? lut : tail.bits;
+}
+
 /* Descriptors in a device table (any batch size)... */
 template <int N, int PPL, int MODE>
 __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel(
     const L3ImageDesc* __restrict__ descs, uint32_t units_per_image, uint32_t images,
     uint32_t* __restrict__ status, uint32_t crop_w, uint32_t crop_h,
-    const uint16_t* __restrict__ lut) {
+    const uint16_t* __restrict__ lut, const typename TailFor<MODE>::type tail) {
     uint32_t image, unit;
     if (!take_work(units_per_image, images, image, unit)) return;
-    decode_unit<N, PPL, MODE>(descs[image], unit, status, crop_w, crop_h, lut);
+    decode_unit<N, PPL, MODE>(descs[image], unit, status, crop_w, crop_h, table_of<MODE>(lut, tail));
 }
 
 /* ...or inside the kernel arguments: no upload, no dependency on a copy, so consecutive
@@ -602,41 +641,27 @@ __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel(
 constexpr int kArgDescsSmall = 32, kArgDescs = 256;
 template <int CAP>
 struct DescPack { L3ImageDesc d[CAP]; };
-static_assert(sizeof(DescPack<kArgDescs>) + 64 <= 32768, "kernel argument segment");
+static_assert(sizeof(DescPack<kArgDescs>) + sizeof(L3Table) + 64 <= 32768, "kernel argument segment");
 
 template <int N, int PPL, int MODE, int CAP>
 __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel_args(
     const DescPack<CAP> pack, uint32_t units_per_image, uint32_t images, uint32_t* __restrict__ status,
-    uint32_t crop_w, uint32_t crop_h, const uint16_t* __restrict__ lut) {
+    uint32_t crop_w, uint32_t crop_h, const uint16_t* __restrict__ lut,
+    const typename TailFor<MODE>::type tail) {
     uint32_t image, unit;
     if (!take_work(units_per_image, images, image, unit)) return;
-    decode_unit<N, PPL, MODE>(pack.d[image], unit, status, crop_w, crop_h, lut);
+    decode_unit<N, PPL, MODE>(pack.d[image], unit, status, crop_w, crop_h, table_of<MODE>(lut, tail));
 }
 
-/* y = (x/255 - mean) / stdv for all 256 byte values of each channel, IEEE
- * binary32 without contraction, rounded to nearest-even to the 16-bit type. */
+/* The table in device memory, for the call that keeps one there. */
 __global__ void l3_build_table_kernel(float m0, float m1, float m2, float s0, float s1, float s2,
                                       int dtype, uint16_t* __restrict__ table) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= 768) return;
-    const uint32_t c = i >> 8, v = i & 255u;
+    const uint32_t c = i >> 8;
     const float mean = c == 0 ? m0 : (c == 1 ? m1 : m2);
     const float stdv = c == 0 ? s0 : (c == 1 ? s1 : s2);
-    const float y = __fdiv_rn(__fsub_rn(__fdiv_rn((float)v, 255.0f), mean), stdv);
-    uint16_t bits;
-    if (dtype == L3_BF16) {
-        uint32_t u = __float_as_uint(y);
-        if ((u & 0x7FFFFFFFu) > 0x7F800000u) {
-            bits = (uint16_t)((u >> 16) | 0x0040u);
-        } else {
-            u += 0x7FFFu + ((u >> 16) & 1u);
-            bits = (uint16_t)(u >> 16);
-        }
-    } else {
-        const _Float16 h = (_Float16)y;
-        bits = __builtin_bit_cast(uint16_t, h);
-    }
-    table[i] = bits;
+    table[i] = normalised_bits(i & 255u, mean, stdv, dtype);
 }
 
 __global__ void l3_fill_u32_kernel(uint32_t* p, uint32_t n, uint32_t value) {
@@ -681,12 +706,11 @@ uint16_t* static_table_of(int device) {
 }
 
 
-typedef void (*decode_kernel_t)(const L3ImageDesc*, uint32_t, uint32_t, uint32_t*, uint32_t, uint32_t,
-                                const uint16_t*);
-typedef void (*decode_kernel_args_small_t)(const DescPack<kArgDescsSmall>, uint32_t, uint32_t, uint32_t*,
-                                           uint32_t, uint32_t, const uint16_t*);
-typedef void (*decode_kernel_args_t)(const DescPack<kArgDescs>, uint32_t, uint32_t, uint32_t*, uint32_t,
-                                     uint32_t, const uint16_t*);
+/* The kernels are launched through argument arrays (hipLaunchKernel): the fused ones take one
+ * argument more than the others, the table. */
+typedef const void* decode_kernel_t;
+typedef const void* decode_kernel_args_small_t;
+typedef const void* decode_kernel_args_t;
 
 struct KernelChoice {
     decode_kernel_t table;        /* descriptors in a device table */
@@ -701,19 +725,19 @@ KernelChoice choice_for_mode(int mode) {
     k.tiles_per_wave = Geom<N, PPL>::TPW;
     switch (mode) {
         case L3_MODE_HWC:
-            k.table = l3_decode_kernel<N, PPL, L3_MODE_HWC>;
-            k.args_small = l3_decode_kernel_args<N, PPL, L3_MODE_HWC, kArgDescsSmall>;
-            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_HWC, kArgDescs>;
+            k.table = reinterpret_cast<const void*>(&l3_decode_kernel<N, PPL, L3_MODE_HWC>);
+            k.args_small = reinterpret_cast<const void*>(&l3_decode_kernel_args<N, PPL, L3_MODE_HWC, kArgDescsSmall>);
+            k.args = reinterpret_cast<const void*>(&l3_decode_kernel_args<N, PPL, L3_MODE_HWC, kArgDescs>);
             break;
         case L3_MODE_CHW:
-            k.table = l3_decode_kernel<N, PPL, L3_MODE_CHW>;
-            k.args_small = l3_decode_kernel_args<N, PPL, L3_MODE_CHW, kArgDescsSmall>;
-            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_CHW, kArgDescs>;
+            k.table = reinterpret_cast<const void*>(&l3_decode_kernel<N, PPL, L3_MODE_CHW>);
+            k.args_small = reinterpret_cast<const void*>(&l3_decode_kernel_args<N, PPL, L3_MODE_CHW, kArgDescsSmall>);
+            k.args = reinterpret_cast<const void*>(&l3_decode_kernel_args<N, PPL, L3_MODE_CHW, kArgDescs>);
             break;
         default:
-            k.table = l3_decode_kernel<N, PPL, L3_MODE_TENSOR>;
-            k.args_small = l3_decode_kernel_args<N, PPL, L3_MODE_TENSOR, kArgDescsSmall>;
-            k.args = l3_decode_kernel_args<N, PPL, L3_MODE_TENSOR, kArgDescs>;
+            k.table = reinterpret_cast<const void*>(&l3_decode_kernel<N, PPL, L3_MODE_TENSOR>);
+            k.args_small = reinterpret_cast<const void*>(&l3_decode_kernel_args<N, PPL, L3_MODE_TENSOR, kArgDescsSmall>);
+            k.args = reinterpret_cast<const void*>(&l3_decode_kernel_args<N, PPL, L3_MODE_TENSOR, kArgDescs>);
             break;
     }
     return k;
@@ -901,53 +925,30 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         hipLaunchKernelGGL(l3_fill_u32_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, d_status,
                            (uint32_t)n, 0u);
     }
+    /* The table of normalised values travels inside the arguments of the fused kernels: the
+     * host works it out (and remembers the last one), so a call depends on no table in device
+     * memory and on no kernel ahead of it, and records the same work under stream capture as
+     * outside it.  Only the call that allocates nothing keeps its table in device memory (the
+     * library's static one, rebuilt by a small kernel ahead of every launch). */
     const uint16_t* table = nullptr;
-    int table_slot = -1;   /* the cache slot this call reads, if any */
+    L3NoTable no_tail;
+    void* tail = &no_tail;
     if (mode == L3_MODE_TENSOR) {
-        /* The table of the 256 normalised values per channel, built by a small kernel on the
-         * call's stream ahead of the kernel that reads it.
-         *  - no_alloc: always built, into the library's static table of this GPU.
-         *  - under stream capture: always built, into a table of its own, so that the graph
-         *    holds the build and replays stand alone.
-         *  - otherwise cached: a slot per (constants, stream) pair; a call that finds its pair
-         *    builds nothing.  A pair that is not there takes the next slot in turn; the kernels
-         *    that still read that slot on another stream are waited for on the device (event
-         *    recorded behind every cached call), never on the host. */
-        const float key[7] = {mean[0], mean[1], mean[2], stdv[0], stdv[1], stdv[2], (float)dtype};
-        uint16_t* build_into = nullptr;
-        hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(stream, &capture) != hipSuccess) return L3_ERR_DEVICE;
         if (no_alloc) {
-            build_into = ctx->static_table;
-        } else if (capture != hipStreamCaptureStatusNone) {
-            build_into = ctx->d_table_capture;
-        } else {
-            int ts = -1;
-            for (int k = 0; k < kSlots && ts < 0; ++k) {
-                const int cand = (ctx->table_cur + k) % kSlots;
-                if (ctx->table_valid[cand] && ctx->table_stream[cand] == stream &&
-                    std::memcmp(ctx->table_key[cand], key, sizeof key) == 0)
-                    ts = cand;
-            }
-            if (ts < 0) {
-                ts = (ctx->table_cur + 1) % kSlots;
-                if (ctx->table_valid[ts] && ctx->table_stream[ts] != stream && ctx->table_used_valid[ts] &&
-                    hipStreamWaitEvent(stream, ctx->table_used[ts], 0) != hipSuccess)
-                    return L3_ERR_DEVICE;
-                build_into = ctx->d_table[ts];
-                std::memcpy(ctx->table_key[ts], key, sizeof key);
-                ctx->table_valid[ts] = true;
-                ctx->table_stream[ts] = stream;
-            }
-            ctx->table_cur = ts;
-            table_slot = ts;
-            table = ctx->d_table[ts];
-        }
-        if (build_into) {
             hipLaunchKernelGGL(l3_build_table_kernel, dim3(3), dim3(256), 0, stream, mean[0], mean[1],
-                               mean[2], stdv[0], stdv[1], stdv[2], dtype, build_into);
-            table = build_into;
+                               mean[2], stdv[0], stdv[1], stdv[2], dtype, ctx->static_table);
+            table = ctx->static_table;
+        } else {
+            const float key[7] = {mean[0], mean[1], mean[2], stdv[0], stdv[1], stdv[2], (float)dtype};
+            if (!ctx->table_valid || std::memcmp(ctx->table_key, key, sizeof key) != 0) {
+                if (l3_normalized_values(mean, stdv, (l3_dtype)dtype, ctx->table_bits) != L3_OK)
+                    return L3_ERR_INVALID_ARG;
+                std::memcpy(ctx->table_key, key, sizeof key);
+                ctx->table_valid = true;
+            }
         }
+        static_assert(sizeof(L3Table) == sizeof ctx->table_bits, "the context's copy is the argument");
+        tail = ctx->table_bits;
     }
     for (int k = 0; k < 3; ++k) {
         const int count = class_begin[k + 1] - class_begin[k];
@@ -955,24 +956,26 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         const uint32_t gx = max_units[k];
         /* one-dimensional grid, rounded up to a multiple of 8 (see take_work) */
         const auto grid_for = [gx](uint64_t images) { return (uint32_t)((gx * images + 7) / 8 * 8); };
+        uint32_t gx_arg = gx;
         if (in_args && count <= kArgDescsSmall) {
             DescPack<kArgDescsSmall> pack;
             std::memcpy(pack.d, stage + class_begin[k], (size_t)count * sizeof(L3ImageDesc));
-            hipLaunchKernelGGL(pick_kernel(kClasses[k], mode).args_small, dim3(grid_for((uint64_t)count)),
-                               dim3(kBlockThreads), 0, stream, pack, gx, (uint32_t)count, d_status, crop_w,
-                               crop_h, table);
+            uint32_t count_arg = (uint32_t)count;
+            void* kernel_args[8] = {&pack, &gx_arg, &count_arg, &d_status, &crop_w, &crop_h, &table, tail};
+            if (hipLaunchKernel(pick_kernel(kClasses[k], mode).args_small, dim3(grid_for((uint64_t)count)),
+                                dim3(kBlockThreads), kernel_args, 0, stream) != hipSuccess)
+                return L3_ERR_DEVICE;
             continue;
         }
         if (in_args) {
             /* 28 KB of arguments: handed over by address, straight from the staging array
              * (which has kArgDescs spare entries behind the last descriptor), so that the
              * block is copied once, by the launch, and never sits on the stack */
-            uint32_t gx_arg = gx, count_arg = (uint32_t)count;
-            void* kernel_args[7] = {stage + class_begin[k], &gx_arg, &count_arg, &d_status,
-                                    &crop_w, &crop_h, &table};
-            if (hipLaunchKernel(reinterpret_cast<const void*>(pick_kernel(kClasses[k], mode).args),
-                                dim3(grid_for((uint64_t)count)), dim3(kBlockThreads), kernel_args, 0,
-                                stream) != hipSuccess)
+            uint32_t count_arg = (uint32_t)count;
+            void* kernel_args[8] = {stage + class_begin[k], &gx_arg, &count_arg, &d_status,
+                                    &crop_w, &crop_h, &table, tail};
+            if (hipLaunchKernel(pick_kernel(kClasses[k], mode).args, dim3(grid_for((uint64_t)count)),
+                                dim3(kBlockThreads), kernel_args, 0, stream) != hipSuccess)
                 return L3_ERR_DEVICE;
             continue;
         }
@@ -981,16 +984,15 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         const int per_launch = (int)std::min<uint64_t>((uint64_t)count, 0x7FFFFF00ull / gx);
         for (int first = 0; first < count; first += per_launch) {
             const int m = count - first < per_launch ? count - first : per_launch;
-            hipLaunchKernelGGL(kern, dim3(grid_for((uint64_t)m)), dim3(kBlockThreads), 0, stream,
-                               d_descs + class_begin[k] + first, gx, (uint32_t)m, d_status, crop_w, crop_h,
-                               table);
+            const L3ImageDesc* first_desc = d_descs + class_begin[k] + first;
+            uint32_t m_arg = (uint32_t)m;
+            void* kernel_args[8] = {&first_desc, &gx_arg, &m_arg, &d_status, &crop_w, &crop_h, &table, tail};
+            if (hipLaunchKernel(kern, dim3(grid_for((uint64_t)m)), dim3(kBlockThreads), kernel_args, 0,
+                                stream) != hipSuccess)
+                return L3_ERR_DEVICE;
         }
     }
     if (hipGetLastError() != hipSuccess) return L3_ERR_DEVICE;
-    if (table_slot >= 0) {
-        if (hipEventRecord(ctx->table_used[table_slot], stream) != hipSuccess) return L3_ERR_DEVICE;
-        ctx->table_used_valid[table_slot] = true;
-    }
     if (slot >= 0) {
         if (hipEventRecord(ctx->done[slot], stream) != hipSuccess) return L3_ERR_DEVICE;
         ctx->pending[slot] = true;
@@ -1024,13 +1026,9 @@ l3_status l3_ctx_create(l3_ctx** out, int device) {
      * make a call allocate */
     ctx->scratch_cap = 3 * kArgDescs;
     ctx->scratch = static_cast<L3ImageDesc*>(std::malloc((ctx->scratch_cap + kArgDescs) * sizeof(L3ImageDesc)));
-    bool ok = ctx->static_table && ctx->scratch &&
-              hipMalloc(reinterpret_cast<void**>(&ctx->d_table_capture), 768 * sizeof(uint16_t)) == hipSuccess;
-    for (int s = 0; s < kSlots && ok; ++s) {
-        ok = hipEventCreateWithFlags(&ctx->done[s], hipEventDisableTiming) == hipSuccess &&
-             hipEventCreateWithFlags(&ctx->table_used[s], hipEventDisableTiming) == hipSuccess &&
-             hipMalloc(reinterpret_cast<void**>(&ctx->d_table[s]), 768 * sizeof(uint16_t)) == hipSuccess;
-    }
+    bool ok = ctx->static_table && ctx->scratch;
+    for (int s = 0; s < kSlots && ok; ++s)
+        ok = hipEventCreateWithFlags(&ctx->done[s], hipEventDisableTiming) == hipSuccess;
     if (!ok) {
         l3_ctx_destroy(ctx);
         return L3_ERR_DEVICE;
@@ -1045,12 +1043,7 @@ void l3_ctx_destroy(l3_ctx* ctx) {
     for (int s = 0; s < kSlots; ++s) {
         if (ctx->pending[s]) (void)hipEventSynchronize(ctx->done[s]);
         if (ctx->done[s]) (void)hipEventDestroy(ctx->done[s]);
-        /* kernels of the last fused calls may still read the slot's table */
-        if (ctx->table_used_valid[s]) (void)hipEventSynchronize(ctx->table_used[s]);
-        if (ctx->table_used[s]) (void)hipEventDestroy(ctx->table_used[s]);
-        if (ctx->d_table[s]) (void)hipFree(ctx->d_table[s]);
     }
-    if (ctx->d_table_capture) (void)hipFree(ctx->d_table_capture);
     release_slots(ctx);
     std::free(ctx->scratch);
     l3_encode_state_free(ctx->enc);

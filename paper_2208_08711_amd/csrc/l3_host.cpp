@@ -112,9 +112,55 @@ void encode_plane_patch(const uint8_t* plane, uint32_t pw, uint32_t ph, bool ori
     sink.flush_to_byte();
 }
 
+/* binary32 -> binary16 bits, round to nearest, ties to even (subnormals, overflow to
+ * infinity; a NaN stays a quiet NaN with the top of its payload) */
+uint16_t f32_to_f16_bits(float f) {
+    uint32_t x;
+    std::memcpy(&x, &f, 4);
+    const uint32_t sign = (x >> 16) & 0x8000u;
+    x &= 0x7FFFFFFFu;
+    if (x > 0x7F800000u) return (uint16_t)(sign | 0x7E00u | ((x >> 13) & 0x01FFu));
+    if (x >= 0x47800000u) return (uint16_t)(sign | 0x7C00u);   /* 65536 and beyond, infinity */
+    if (x >= 0x38800000u) {                                    /* a normal binary16: 2^-14 and beyond */
+        uint32_t h = (((x >> 23) - 112u) << 10) | ((x & 0x007FFFFFu) >> 13);
+        const uint32_t rest = x & 0x1FFFu;
+        if (rest > 0x1000u || (rest == 0x1000u && (h & 1u))) ++h;   /* may carry up to infinity: correct */
+        return (uint16_t)(sign | h);
+    }
+    if (x < 0x33000000u) return (uint16_t)sign;                /* below 2^-25: zero (2^-25 itself ties to zero) */
+    const uint32_t mant = (x & 0x007FFFFFu) | 0x00800000u;     /* a subnormal binary16: units of 2^-24 */
+    const uint32_t shift = 126u - (x >> 23);                   /* 14 .. 24 */
+    uint32_t h = mant >> shift;
+    const uint32_t rest = mant & ((1u << shift) - 1u), half = 1u << (shift - 1u);
+    if (rest > half || (rest == half && (h & 1u))) ++h;
+    return (uint16_t)(sign | h);
+}
+
+uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
 }  // namespace
 
 extern "C" {
+
+l3_status l3_normalized_values(const float mean[3], const float stdv[3], l3_dtype dtype,
+                               uint16_t out[768]) {
+    if (!mean || !stdv || !out || (dtype != L3_BF16 && dtype != L3_FP16)) return L3_ERR_INVALID_ARG;
+    for (int c = 0; c < 3; ++c)
+        for (int v = 0; v < 256; ++v) {
+            /* three roundings, none fused: the build switches contraction off */
+            const float scaled = (float)v / 255.0f;
+            const float centred = scaled - mean[c];
+            const float y = centred / stdv[c];
+            out[c * 256 + v] = dtype == L3_BF16 ? f32_to_bf16_bits(y) : f32_to_f16_bits(y);
+        }
+    return L3_OK;
+}
 
 const char* l3_status_string(l3_status s) {
     switch (s) {

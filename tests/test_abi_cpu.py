@@ -76,6 +76,35 @@ def test_product_encoder_original_filter_matches_oracle_bytes():
             assert len(a) <= l3.encode_bound(im.shape[1], im.shape[0], patch)
 
 
+def test_normalized_values_match_the_oracle_and_torch():
+    """l3_normalized_values (what the fused kernels look pixels up in) against the oracle's
+    epilogue on a 1 x 256 image holding every byte value, and against PyTorch CPU ops; the
+    constants reach binary16 subnormals, ties, overflow to infinity and negative values."""
+    import torch
+    ramp = np.arange(256, dtype=np.uint8)[None, :, None].repeat(3, 2)
+    cases = [(synth.IMAGENET_MEAN, synth.IMAGENET_STD), ((0.0, 0.5, 1.0), (1.0, 0.25, 4.0)),
+             ((0.5, 0.5, 0.5), (1e-5, 7e-6, 1.5e-5)),            # binary16 overflows to infinity
+             ((0.0, 0.0, 0.0), (16777216.0, 65536.0 * 3, 5e7)),  # binary16 subnormals and zero
+             ((0.3, 0.7, 0.1), (-0.2, 1e3, 1024.0)), ((1e-3, 2.0, -1.0), (3.0, 0.1, 1e-2))]
+    rng = np.random.default_rng(5)
+    for _ in range(40):
+        cases.append((tuple(rng.uniform(-1, 2, 3)), tuple(10.0 ** rng.uniform(-6, 8, 3))))
+    for mean, stdv in cases:
+        for dtype, tdt in ((l3.BF16, torch.bfloat16), (l3.FP16, torch.float16)):
+            got = l3.normalized_values(mean, stdv, dtype)
+            want = oracle.crop_normalize(ramp, 0, 0, False, 256, 1, mean, stdv, dtype)[:, 0, :]
+            assert np.array_equal(got, want), (mean, stdv, dtype)
+            v = torch.arange(256, dtype=torch.float32)
+            for c in range(3):
+                y = (v / 255.0 - torch.tensor(mean[c], dtype=torch.float32)) / torch.tensor(stdv[c], dtype=torch.float32)
+                ref = y.to(tdt).view(torch.int16).numpy().view(np.uint16)
+                assert np.array_equal(got[c], ref), (mean, stdv, dtype, c)
+    m = (ctypes.c_float * 3)(0, 0, 0)
+    out = (ctypes.c_uint16 * 768)()
+    lib = ctypes.CDLL(l3.library_path())
+    assert lib.l3_normalized_values(m, m, 2, out) == 1 and lib.l3_normalized_values(None, m, 0, out) == 1
+
+
 def test_encode_cpu_errors():
     lib = ctypes.CDLL(l3.library_path())
     lib.l3_encode_cpu.restype = ctypes.c_int
