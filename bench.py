@@ -29,7 +29,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 VALU_ISSUE_PER_S = 256 * 4 * 2.4e9 / 4      # wave instructions per second: 1024 SIMDs, one per 4 cycles
-KERNEL_SOURCES = ("paper_2208_08711_amd/csrc/l3_device.hip", "paper_2208_08711_amd/csrc/l3_gfx950.h")
+KERNEL_SOURCES = ("paper_2208_08711_amd/csrc/l3_device.hip", "paper_2208_08711_amd/csrc/l3_gfx950.h",
+                  "paper_2208_08711_amd/csrc/l3_kernel_parts.h")
 
 
 def kernel_source_stamp():

@@ -49,6 +49,7 @@
 #include "l3_internal.h"
 #include "l3_ctx.h"
 #include "l3_gfx950.h"
+#include "l3_kernel_parts.h"
 
 namespace {
 
@@ -84,21 +85,16 @@ struct Geom {
  * RING bytes).  Three steps, so that the LDS address can be computed one row
  * ahead and the read issued long before its result is needed.  Rings are
  * addressed by their 32-bit LDS byte address. */
-typedef __attribute__((address_space(3))) const uint32_t lds_const_u32;
-struct RingWords { uint32_t lo, hi; };
+typedef LdsPair RingWords;
 template <int RING>
 __device__ __forceinline__ uint32_t ring_where(uint32_t ring_lds, uint32_t bit) {
     static_assert((RING & (RING - 1)) == 0, "ring size is a power of two");
     uint32_t word = __builtin_amdgcn_ubfe(bit, 5, __builtin_ctz(RING / 4));
-    asm("" : "+v"(word));            /* keep bfe + shift-add: two instructions, not three */
+    L3_OPAQUE_VGPR(word);            /* keep bfe + shift-add: two instructions, not three */
     return (word << 2) + ring_lds;
 }
 __device__ __forceinline__ RingWords ring_fetch(uint32_t where) {
-    lds_const_u32* p = reinterpret_cast<lds_const_u32*>(where);
-    RingWords v;
-    v.lo = p[0];
-    v.hi = p[1];   /* may be the mirror word behind the ring */
-    return v;
+    return lds_read_pair(where);   /* the second word may be the mirror word behind the ring */
 }
 __device__ __forceinline__ uint32_t ring_align(RingWords v, uint32_t bit) {
     return __builtin_amdgcn_alignbit(v.hi, v.lo, bit);   /* ({hi,lo} >> (bit & 31)) */
@@ -275,7 +271,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     uint32_t w, w2, K, base2, xbit[NW], wmax = 0;
     uint32_t xwhere[NW];   /* LDS addresses of the words holding this lane's deltas of the open row */
     uint32_t hwhere;       /* LDS address of the words holding the record after the open row */
-    const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)ring;
+    const uint32_t ring_lds = lds_address_of(ring);
 
     /* Opens the row whose record (4-bit width, 8-bit base) is at bitpos: works out
      * where this lane's deltas are (4w <= 32 contiguous bits per word of 4 pixels) and
@@ -308,8 +304,13 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     uint32_t img_width = d.width;
     int32_t win_x0 = d.crop_x0, win_y0 = d.crop_y0;
     uint32_t win_flip = d.flip;
-    asm volatile("" : "+s"(out_base), "+s"(out_row_stride), "+s"(out_plane_stride), "+s"(img_width),
-                      "+s"(win_x0), "+s"(win_y0), "+s"(win_flip));
+    L3_KEEP_SGPR(out_base);
+    L3_KEEP_SGPR(out_row_stride);
+    L3_KEEP_SGPR(out_plane_stride);
+    L3_KEEP_SGPR(img_width);
+    L3_KEEP_SGPR(win_x0);
+    L3_KEEP_SGPR(win_y0);
+    L3_KEEP_SGPR(win_flip);
     /* lane l takes the 4-pixel words l, l + 64, ... of the wave's strip; how many of
      * their pixels exist does not change from row to row */
     uint32_t word_x[NW], word_valid[NW], word_off[NW];
@@ -349,7 +350,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                  * store's offset register (kept opaque here so that it is not widened and
                  * added with vector instructions ahead of time) */
                 uint32_t column = word_off[pass];
-                asm volatile("" : "+v"(column));
+                L3_KEEP_VGPR(column);
                 global_u8* row = reinterpret_cast<global_u8*>((uintptr_t)(out_base + (uint64_t)y * out_row_stride));
                 const uint32_t o0 = pr, o1 = pg, o2 = pb;
                 if (nvalid == 4) {
@@ -377,7 +378,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                     global_u8* row = reinterpret_cast<global_u8*>(
                         (uintptr_t)(out_base + (uint64_t)ch * out_plane_stride + (uint64_t)y * out_row_stride));
                     uint32_t column = word_off[pass];
-                    asm volatile("" : "+v"(column));
+                    L3_KEEP_VGPR(column);
                     if (nvalid == 4) {
                         __builtin_nontemporal_store(word, reinterpret_cast<global_u32_any*>(row + column));
                     } else if (nvalid) {
@@ -413,7 +414,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                     const size_t plane = (size_t)crop_h * crop_w;
                     if (whole) {
                         uint32_t col = (uint32_t)(win_flip ? (int32_t)crop_w - 4 - col0 : col0);
-                        asm volatile("" : "+v"(col));      /* stays the store's 32-bit offset */
+                        L3_KEEP_VGPR(col);      /* stays the store's 32-bit offset */
 #pragma unroll
                         for (int ch = 0; ch < 3; ++ch) {
                             const uint32_t e01 = __builtin_bit_cast(uint32_t, q[ch][0]);
@@ -518,7 +519,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
             global_u8* row = reinterpret_cast<global_u8*>(
                 (uintptr_t)(out_base + (uint64_t)c * out_plane_stride + (uint64_t)y * out_row_stride));
             uint32_t column = word_off[0];
-            asm volatile("" : "+v"(column));
+            L3_KEEP_VGPR(column);
             if (word_valid[0] == 4) {
                 __builtin_nontemporal_store(word[0], reinterpret_cast<global_u32_any*>(row + column));
             } else if (word_valid[0]) {

@@ -33,6 +33,7 @@
 
 #include "l3_ctx.h"
 #include "l3_gfx950.h"
+#include "l3_kernel_parts.h"
 
 namespace {
 

@@ -1,7 +1,9 @@
 /*
- * gfx950 building blocks shared by the decoder and the encoder kernels of the L3
- * library: vector and address-space types, lane shifts, and the custom Paeth
- * predictor (arxiv 2208.08711 Section 4.2) on packed pairs of 16-bit fields.
+ * gfx950 primitives of the L3 kernels: vector and address-space types, lane shifts, packed
+ * 16-bit operations, LDS addressing by 32-bit address, register pinning.  Everything in the
+ * decoder that names the target sits here or is an amdgcn builtin; its own logic
+ * (l3_kernel_parts.h, l3_device.hip) is written on top of these names.  (A host build of the
+ * decode kernels for the sanitizers replaces this file alone: tests/native/kernel_cpu.)
  * Device code only; every translation unit gets its own copy.
  */
 #ifndef L3_GFX950_H
@@ -58,76 +60,50 @@ __device__ __forceinline__ uint32_t pk_mad_u16_by_low(uint32_t a, uint32_t b, ui
     return d;
 }
 
-/* Section 4.2, custom Paeth filter, on NP registers of two pixels at once (16-bit
- * fields holding 0..255).  Value-wise the nearest of TL, TR, T to TL + TR - T is:
- * with lo = min(TL,TR), hi = max(TL,TR), dl = T - lo, dh = hi - T (signed):
- * lo if dl >= 2*dh, else hi if dh >= 2*dl, else T.  The stated tie order
- * (TL, TR, T) only ever chooses between equal values, except T against a
- * neighbour, where the neighbour wins: that is the ">=" above.
- * `border` has all ones in the fields whose pixel sits in the first or last
- * column of its patch, where the prediction is T.  The registers are worked on
- * in lockstep so that dependent packed instructions are not adjacent. */
-template <int NP>
-__device__ __forceinline__ void predict_pairs(const uint32_t (&TL)[NP], const uint32_t (&TR)[NP],
-                                              const uint32_t (&T)[NP], const uint32_t (&border)[NP],
-                                              uint32_t (&pred)[NP]) {
-    uint32_t L[NP], H[NP], dl[NP], dh[NP], not_lo[NP], not_hi[NP];
-    const uint32_t minus2 = 0xFFFEFFFEu;
-#pragma unroll
-    for (int j = 0; j < NP; ++j)
-        L[j] = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2, TL[j]),
-                                                                      __builtin_bit_cast(u16x2, TR[j])));
-#pragma unroll
-    for (int j = 0; j < NP; ++j)
-        H[j] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, TL[j]),
-                                                                      __builtin_bit_cast(u16x2, TR[j])));
-#pragma unroll
-    for (int j = 0; j < NP; ++j)
-        dl[j] = __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, T[j]) -
-                                                     __builtin_bit_cast(u16x2, L[j])));
-#pragma unroll
-    for (int j = 0; j < NP; ++j)
-        dh[j] = __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, H[j]) -
-                                                     __builtin_bit_cast(u16x2, T[j])));
-#pragma unroll
-    for (int j = 0; j < NP; ++j) not_lo[j] = pk_mad_i16(dh[j], minus2, dl[j]);   /* dl - 2 dh */
-#pragma unroll
-    for (int j = 0; j < NP; ++j) not_hi[j] = pk_mad_i16(dl[j], minus2, dh[j]);   /* dh - 2 dl */
-#pragma unroll
-    for (int j = 0; j < NP; ++j)
-        not_lo[j] = __builtin_bit_cast(uint32_t, (s16x2)(__builtin_bit_cast(s16x2, not_lo[j]) >> 15));
-#pragma unroll
-    for (int j = 0; j < NP; ++j)
-        not_hi[j] = __builtin_bit_cast(uint32_t, (s16x2)(__builtin_bit_cast(s16x2, not_hi[j]) >> 15));
-#pragma unroll
-    for (int j = 0; j < NP; ++j) asm("" : "+v"(not_lo[j]), "+v"(not_hi[j]));   /* keep the masks packed */
-    /* bitop3 0xCA: first ? second : third */
-#pragma unroll
-    for (int j = 0; j < NP; ++j) pred[j] = __builtin_amdgcn_bitop3_b32(not_hi[j], T[j], H[j], 0xCA);
-#pragma unroll
-    for (int j = 0; j < NP; ++j) pred[j] = __builtin_amdgcn_bitop3_b32(not_lo[j], pred[j], L[j], 0xCA);
-#pragma unroll
-    for (int j = 0; j < NP; ++j) pred[j] = __builtin_amdgcn_bitop3_b32(border[j], T[j], pred[j], 0xCA);
+/* ---- LDS by 32-bit address ------------------------------------------------ */
+
+typedef __attribute__((address_space(3))) const uint32_t lds_const_u32;
+struct LdsPair { uint32_t lo, hi; };
+__device__ __forceinline__ uint32_t lds_address_of(const uint32_t* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const uint32_t*)p;
 }
+/* the two consecutive words at LDS address `where` (one ds_read2_b32) */
+__device__ __forceinline__ LdsPair lds_read_pair(uint32_t where) {
+    lds_const_u32* p = reinterpret_cast<lds_const_u32*>(where);
+    LdsPair v;
+    v.lo = p[0];
+    v.hi = p[1];
+    return v;
+}
+
+__device__ __forceinline__ uint32_t lds_read_u32(uint32_t where) {
+    return *reinterpret_cast<lds_const_u32*>(where);
+}
+__device__ __forceinline__ u32x2 lds_read_u32x2(uint32_t where) {      /* 8-byte aligned */
+    return *reinterpret_cast<__attribute__((address_space(3))) const u32x2*>(where);
+}
+__device__ __forceinline__ u32x4 lds_read_u32x4(uint32_t where) {      /* 16-byte aligned */
+    return *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>(where);
+}
+__device__ __forceinline__ void lds_write_u32x2(uint32_t where, u32x2 v) {
+    *reinterpret_cast<__attribute__((address_space(3))) u32x2*>(where) = v;
+}
+__device__ __forceinline__ void lds_write_u32x4(uint32_t where, u32x4 v) {
+    *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(where) = v;
+}
+
+/* ---- keeping a value where it is ------------------------------------------ */
+
+/* The value becomes opaque to the optimiser and stays in a vector (scalar) register: used
+ * where the compiler would otherwise widen, rematerialise or reload it at a bad place. */
+#define L3_KEEP_VGPR(x) asm volatile("" : "+v"(x))
+#define L3_KEEP_SGPR(x) asm volatile("" : "+s"(x))
+#define L3_OPAQUE_VGPR(x) asm("" : "+v"(x))     /* the same, free to move or vanish with its value */
 
 __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-/* Which (image, unit) a workgroup takes.  The grid is one-dimensional, a multiple of 8
- * long, and the hardware hands consecutive workgroups to the 8 XCDs in turn (workgroup L
- * runs on XCD L mod 8).  Work item number (L mod 8) * grid/8 + L / 8 therefore gives every
- * XCD one contiguous eighth of the (image, unit) sequence: neighbouring strips, whose
- * streams and output rows share cache lines, meet in the same L2. */
-__device__ __forceinline__ bool take_work(uint32_t units_per_image, uint32_t images, uint32_t& image,
-                                          uint32_t& unit) {
-    const uint32_t eighth = gridDim.x >> 3;
-    const uint32_t item = (blockIdx.x & 7u) * eighth + (blockIdx.x >> 3);
-    image = item / units_per_image;
-    unit = item - image * units_per_image;
-    return image < images;
 }
 
 }  // namespace
