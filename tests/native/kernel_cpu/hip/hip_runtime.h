@@ -114,6 +114,21 @@ inline std::map<const void*, std::function<void(void**)>>& registry() {
     static std::map<const void*, std::function<void(void**)>> r;
     return r;
 }
+/* every block of "device" memory that is alive: address -> bytes (what hipMalloc and
+ * hipHostMalloc gave out, device symbols that were asked for, and what the harness adds) */
+inline std::map<const void*, size_t>& regions() {
+    static std::map<const void*, size_t> r;
+    return r;
+}
+inline const void* symbol(const void* p, size_t n) {
+    regions()[p] = n;
+    return p;
+}
+/* called ahead of every hipLaunchKernel, if set (the harness can record the launch) */
+inline std::function<void(const void*, dim3, dim3, void**)>& launch_observer() {
+    static std::function<void(const void*, dim3, dim3, void**)> f;
+    return f;
+}
 
 }  // namespace l3cpu
 
@@ -146,8 +161,16 @@ constexpr unsigned hipEventDisableTiming = 2, hipHostMallocDefault = 0;
 inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
 inline hipError_t hipSetDevice(int) { return hipSuccess; }
 inline hipError_t hipGetDeviceCount(int* n) { *n = 1; return hipSuccess; }
-inline hipError_t hipMalloc(void** p, size_t n) { *p = std::malloc(n ? n : 1); return *p ? hipSuccess : 2; }
-inline hipError_t hipFree(void* p) { std::free(p); return hipSuccess; }
+inline hipError_t hipMalloc(void** p, size_t n) {
+    *p = std::malloc(n ? n : 1);
+    if (*p) l3cpu::regions()[*p] = n;
+    return *p ? hipSuccess : 2;
+}
+inline hipError_t hipFree(void* p) {
+    l3cpu::regions().erase(p);
+    std::free(p);
+    return hipSuccess;
+}
 inline hipError_t hipHostMalloc(void** p, size_t n, unsigned) { return hipMalloc(p, n); }
 inline hipError_t hipHostFree(void* p) { return hipFree(p); }
 inline hipError_t hipEventCreateWithFlags(hipEvent_t* e, unsigned) {
@@ -158,7 +181,7 @@ inline hipError_t hipEventDestroy(hipEvent_t e) { std::free(e); return hipSucces
 inline hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }   /* launches are synchronous */
 inline hipError_t hipEventSynchronize(hipEvent_t) { return hipSuccess; }
 inline hipError_t hipGetLastError() { return hipSuccess; }
-#define HIP_SYMBOL(x) (&(x))
+#define HIP_SYMBOL(x) l3cpu::symbol(&(x), sizeof(x))
 inline hipError_t hipGetSymbolAddress(void** p, const void* symbol) {
     *p = const_cast<void*>(symbol);
     return hipSuccess;
@@ -166,6 +189,7 @@ inline hipError_t hipGetSymbolAddress(void** p, const void* symbol) {
 inline hipError_t hipLaunchKernel(const void* kernel, dim3 grid, dim3 block, void** args, size_t, hipStream_t) {
     auto it = l3cpu::registry().find(kernel);
     if (it == l3cpu::registry().end()) return 98;
+    if (l3cpu::launch_observer()) l3cpu::launch_observer()(kernel, grid, block, args);
     void** a = args;
     auto call = it->second;
     l3cpu::launch(grid, block, [call, a] { call(a); });

@@ -7,6 +7,10 @@
  * ThreadSanitizer any two accesses to LDS or to the outputs that no barrier orders do.
  *
  * usage: kernel_cpu <case file>       (written by tests/test_kernel_cpu_build.py)
+ * With L3CPU_RECORD=<directory> in the environment every decode launch is recorded there
+ * (which kernel, grid, argument block, every live buffer with its address and contents) and
+ * so are the buffers after the run: what tests/native/isa_interp/interp.py needs to run the
+ * same launch from the compiler's machine code.
  * Test infrastructure.
  */
 #include <hip/hip_runtime.h>
@@ -28,10 +32,57 @@ void l3_ablation_state_free(L3AblationState*) {}
 
 namespace {
 
+/* what a recorded launch says about its kernel: patch size, mode, how the descriptors travel
+ * (0 device table, 1 up to 32 in the arguments, 2 up to 256), and the sizes of its first and
+ * last argument (the others are gx, count, status, crop_w, crop_h, table pointer) */
+struct KernelFacts { int n, mode, kind; size_t first_bytes, tail_bytes; };
+std::map<const void*, KernelFacts> g_facts;
+int g_recorded = 0;
+
+void write_regions(FILE* f) {
+    const uint64_t count = l3cpu::regions().size();
+    std::fwrite(&count, 8, 1, f);
+    for (const auto& r : l3cpu::regions()) {
+        const uint64_t address = (uint64_t)(uintptr_t)r.first, bytes = r.second;
+        std::fwrite(&address, 8, 1, f);
+        std::fwrite(&bytes, 8, 1, f);
+        std::fwrite(r.first, 1, r.second, f);
+    }
+}
+
+void record_launch(const char* dir, const void* kernel, dim3 grid, dim3 block, void** a) {
+    const KernelFacts k = g_facts.at(kernel);
+    FILE* f = std::fopen((std::string(dir) + "/launch_" + std::to_string(g_recorded++) + ".bin").c_str(), "wb");
+    if (!f) std::abort();
+    const int32_t head[6] = {k.n, k.mode, k.kind, (int32_t)grid.x, (int32_t)block.x, 0};
+    std::fwrite(head, 4, 6, f);
+    /* the argument block as the GPU sees it: every argument at its natural alignment */
+    std::vector<uint8_t> block_bytes(k.first_bytes + 32 + k.tail_bytes, 0);
+    std::memcpy(block_bytes.data(), a[0], k.first_bytes);
+    const size_t o = k.first_bytes;
+    std::memcpy(&block_bytes[o], a[1], 4);
+    std::memcpy(&block_bytes[o + 4], a[2], 4);
+    std::memcpy(&block_bytes[o + 8], a[3], 8);
+    std::memcpy(&block_bytes[o + 16], a[4], 4);
+    std::memcpy(&block_bytes[o + 20], a[5], 4);
+    std::memcpy(&block_bytes[o + 24], a[6], 8);
+    std::memcpy(&block_bytes[o + 32], a[7], k.tail_bytes);
+    const uint64_t bytes = block_bytes.size();
+    std::fwrite(&bytes, 8, 1, f);
+    std::fwrite(block_bytes.data(), 1, bytes, f);
+    write_regions(f);
+    std::fclose(f);
+}
+
 template <int N, int MODE>
 void register_kernels() {
     typedef typename TailFor<MODE>::type Tail;
     auto& reg = l3cpu::registry();
+    g_facts[reinterpret_cast<const void*>(&l3_decode_kernel<N, 4, MODE>)] = {N, MODE, 0, 8, sizeof(Tail)};
+    g_facts[reinterpret_cast<const void*>(&l3_decode_kernel_args<N, 4, MODE, kArgDescsSmall>)] =
+        {N, MODE, 1, sizeof(DescPack<kArgDescsSmall>), sizeof(Tail)};
+    g_facts[reinterpret_cast<const void*>(&l3_decode_kernel_args<N, 4, MODE, kArgDescs>)] =
+        {N, MODE, 2, sizeof(DescPack<kArgDescs>), sizeof(Tail)};
     reg[reinterpret_cast<const void*>(&l3_decode_kernel<N, 4, MODE>)] = [](void** a) {
         l3_decode_kernel<N, 4, MODE>(*static_cast<const L3ImageDesc**>(a[0]), *static_cast<uint32_t*>(a[1]),
                                      *static_cast<uint32_t*>(a[2]), *static_cast<uint32_t**>(a[3]),
@@ -151,6 +202,17 @@ int main(int argc, char** argv) {
     uint32_t* status = static_cast<uint32_t*>(std::malloc(sizeof(uint32_t) * (size_t)n));
     std::memset(status, 0xFF, sizeof(uint32_t) * (size_t)n);
 
+    const char* record_dir = std::getenv("L3CPU_RECORD");
+    if (record_dir) {
+        for (size_t i = 0; i < blocks.size(); ++i)
+            l3cpu::regions()[blocks[i]] = ((i * 7 + 1) % 16 + items[i].file_len + 15) / 16 * 16;
+        for (size_t i = 0; i < outs.size(); ++i) l3cpu::regions()[outs[i]] = out_bytes[i];
+        if (tensor) l3cpu::regions()[tensor] = tensor_bytes;
+        l3cpu::regions()[status] = sizeof(uint32_t) * (size_t)n;
+        l3cpu::launch_observer() = [record_dir](const void* kernel, dim3 grid, dim3 block, void** a) {
+            record_launch(record_dir, kernel, grid, block, a);
+        };
+    }
     l3_ctx* ctx = nullptr;
     if (l3_ctx_create(&ctx, 0) != L3_OK) return 2;
     l3_status st;
@@ -163,6 +225,12 @@ int main(int argc, char** argv) {
         st = l3_decode_crop_normalize_batch_noalloc(ctx, items.data(), crops.data(), n, crop_w, crop_h, mean,
                                                     stdv, (l3_dtype)dtype, tensor, status, nullptr);
     if (st != L3_OK) { std::fprintf(stderr, "call failed: %s\n", l3_status_string(st)); return 1; }
+    if (record_dir) {
+        FILE* f = std::fopen((std::string(record_dir) + "/after.bin").c_str(), "wb");
+        if (!f) std::abort();
+        write_regions(f);
+        std::fclose(f);
+    }
     l3_ctx_destroy(ctx);
 
     int rc = 0;
