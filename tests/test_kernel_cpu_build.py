@@ -8,6 +8,7 @@ tests/test_gpu_parity.py."""
 import os
 import struct
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -39,9 +40,11 @@ def exes(tmp_path_factory):
     if not os.path.exists(CLANG):
         pytest.skip("no clang++ with sanitizer runtimes")
     tmp = str(tmp_path_factory.mktemp("kernel_cpu"))
-    return {"asan": build(tmp, "kernel_cpu_asan", ["-fsanitize=address,undefined",
-                                                    "-fno-sanitize-recover=undefined"]),
-            "tsan": build(tmp, "kernel_cpu_tsan", ["-fsanitize=thread"]), "tmp": tmp}
+    with ThreadPoolExecutor(2) as pool:      # the two builds side by side
+        asan = pool.submit(build, tmp, "kernel_cpu_asan", ["-fsanitize=address,undefined",
+                                                            "-fno-sanitize-recover=undefined"])
+        tsan = pool.submit(build, tmp, "kernel_cpu_tsan", ["-fsanitize=thread"])
+        return {"asan": asan.result(), "tsan": tsan.result(), "tmp": tmp}
 
 
 def write_case(path, mode, images, patch, crops=None, crop=(0, 0), dtype=0, pad_cols=5):
@@ -148,13 +151,18 @@ def test_planted_mistakes_are_seen(exes):
         ("overwrite", "asan", "reinterpret_cast<global_u32x3_any*>(row + column)",
          "reinterpret_cast<global_u32x3_any*>(row + column + 4)", "MISMATCH"),
     ]
-    for name, kind, old, new, report in plants:
+    def build_plant(plant):
+        name, kind, old, new, report = plant
         assert src.count(old) == 1, name
         path = os.path.join(exes["tmp"], f"l3_device_{name}.hip")
         with open(path, "w") as f:
             f.write(src.replace(old, new))
         flags = (["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"] if kind == "asan"
                  else ["-fsanitize=thread"])
-        exe = build(exes["tmp"], f"kernel_cpu_{name}", flags, kernel_source=path)
+        return build(exes["tmp"], f"kernel_cpu_{name}", flags, kernel_source=path)
+
+    with ThreadPoolExecutor(3) as pool:
+        built = list(pool.map(build_plant, plants))
+    for (name, kind, old, new, report), exe in zip(plants, built):
         r = execute(exe, case)
         assert r.returncode != 0 and report in r.stderr, (name, r.returncode, r.stderr[-1500:])

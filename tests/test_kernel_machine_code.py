@@ -10,6 +10,7 @@ import re
 import struct
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 import pytest
 
@@ -35,10 +36,12 @@ def built(tmp_path_factory):
         pytest.skip("needs hipcc and clang++")
     tmp = str(tmp_path_factory.mktemp("machine_code"))
     asm, ir = os.path.join(tmp, "l3_device.s"), os.path.join(tmp, "l3_device.ll")
-    subprocess.run([HIPCC, *FLAGS, "-S", "-o", asm], check=True)
-    subprocess.run([HIPCC, *FLAGS, "-emit-llvm", "-S", "-o", ir], check=True)
-    return {"tmp": tmp, "asm": open(asm).read(), "ir": open(ir).read(),
-            "harness": host_build.build(tmp, "kernel_cpu_plain", [])}
+    with ThreadPoolExecutor(3) as pool:      # the three builds side by side
+        jobs = [pool.submit(subprocess.run, [HIPCC, *FLAGS, "-S", "-o", asm], check=True),
+                pool.submit(subprocess.run, [HIPCC, *FLAGS, "-emit-llvm", "-S", "-o", ir], check=True),
+                pool.submit(host_build.build, tmp, "kernel_cpu_plain", [])]
+        harness = [j.result() for j in jobs][2]
+    return {"tmp": tmp, "asm": open(asm).read(), "ir": open(ir).read(), "harness": harness}
 
 
 def kernel_text(asm, n, mode, kind):
