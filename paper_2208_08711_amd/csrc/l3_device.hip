@@ -78,6 +78,7 @@ struct Geom {
     static_assert(CHUNK >= P * ROW_MAX, "refill keeps up with the longest rows");
     static_assert(CHUNK >= 15 + AHEAD, "first refill covers the first period");
     static_assert(RING >= AHEAD + CHUNK + ROW_MAX + 8, "ring holds a row, a period ahead and a refill");
+    static_assert(GPL == 2 && RING == 2 * CHUNK, "two granules per lane and refill, which never wrap inside one");
 };
 
 /* The 32 stream bits starting at bit `bit` of a ring live in two aligned words
@@ -242,7 +243,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
             *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + idx) = pf[t];
             if (idx == 0) *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + RING) = pf[t];
         }
-        fill = CHUNK;
+        fill = CHUNK + xl * 16;   /* this lane's first granule of the chunk in pf: see the ring top-up */
 #pragma unroll
         for (int t = 0; t < GPL; ++t) pf[t] = load_granule(origin, CHUNK + (t * LPT + xl) * 16, limit);
     }
@@ -554,6 +555,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
      * tenant of the buffer.  (With two buffers a wave could still be writing out period
      * k-2 when an early one starts to park period k.) */
     uint32_t buf = 0, prev_buf = 0;
+    const uint32_t need_lane = G::AHEAD + xl * 16;   /* see the ring top-up */
     for (uint32_t r = 0; r < ph; r += P) {
         const uint32_t rows = min((uint32_t)P, ph - r);
         if (r >= next_drop) {
@@ -582,20 +584,26 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
         if (rows > 1) do_row(park + 3 * QW, y0 + r + 1);
         if (rows > 2) {
             if (r + P < ph) {
-                /* top the ring up for rows r+3 .. r+5; bitpos is the record of row r+3 */
-                const uint32_t need = (bitpos >> 3) + G::AHEAD;
+                /* top the ring up for rows r+3 .. r+5; bitpos is the record of row r+3.  `fill`
+                 * counts this lane's own first granule of the chunk held in pf (the stream's
+                 * fill level plus 16 bytes per lane of the group), so that ring place and load
+                 * address follow from it directly.  A chunk is half the ring and starts at a
+                 * multiple of its size, so its granules never wrap inside one refill: the
+                 * lane's second granule sits CHUNK / 2 behind its first, in the ring and in
+                 * the stream.  What pf holds beyond the stream's last granule is left as it
+                 * was: nothing that is decoded reads it. */
+                const uint32_t need = (bitpos >> 3) + need_lane;
                 if (fill < need) {
-#pragma unroll
-                    for (int t = 0; t < GPL; ++t) {
-                        const uint32_t idx = (fill + (t * LPT + xl) * 16) & (RING - 1);
-                        *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + idx) = pf[t];
-                        if (t == 0 && idx == 0)
-                            *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + RING) = pf[t];
-                    }
+                    const uint32_t idx = fill & (RING - 1);
+                    uint8_t* at = reinterpret_cast<uint8_t*>(ring) + idx;
+                    *reinterpret_cast<u32x4*>(at) = pf[0];
+                    *reinterpret_cast<u32x4*>(at + CHUNK / 2) = pf[1];
+                    if (idx == 0) *reinterpret_cast<u32x4*>(at + RING) = pf[0];
                     fill += CHUNK;
-#pragma unroll
-                    for (int t = 0; t < GPL; ++t)
-                        pf[t] = load_granule(origin, fill + (t * LPT + xl) * 16, limit);
+                    if (fill < limit)
+                        pf[0] = *reinterpret_cast<global_const_u32x4*>((uintptr_t)(origin + fill));
+                    if (fill + CHUNK / 2 < limit)
+                        pf[1] = *reinterpret_cast<global_const_u32x4*>((uintptr_t)(origin + fill + CHUNK / 2));
                 }
                 wave_lds_fence();
             }
