@@ -13,10 +13,11 @@ would run.  Waves run one after the other between barriers, which is the interle
 kind to a missing synchronisation.  Only the instructions the decode kernels use are known; an
 unknown one stops the run by name.  Registers start poisoned, LDS starts as garbage.
 
-usage: interp.py <kernel.s> <launch.bin> [after.bin] [--wg=first:last]
+usage: interp.py <kernel.s> <launch.bin> [after.bin] [--wg=first:last] [--hist=file]
   kernel.s    one kernel's text, from its label to .end_amdhsa_kernel
   launch.bin  a launch recorded by tests/native/kernel_cpu (L3CPU_RECORD)
   after.bin   the buffers after the host build's run
+  --hist      writes, per instruction, how many times a wave executed it
 Test infrastructure (tests/test_kernel_machine_code.py)."""
 import re
 import struct
@@ -151,6 +152,7 @@ class Emu:
         self.lds = bytearray(lds_size)
         self.lds_oob = 0
         self.count = 0
+        self.executed = {}      # instruction index -> times a wave executed it
 
     # ---- operand access -------------------------------------------------
     def sreg_index(self, t):
@@ -257,6 +259,7 @@ class Emu:
         ins = self.insts[w.pc]
         w.pc += 1
         self.count += 1
+        self.executed[w.pc - 1] = self.executed.get(w.pc - 1, 0) + 1
         op, a, mods = ins.op, ins.args, ins.mods
         base = op
         for suf in ("_e32", "_e64", "_dpp", "_sdwa"):
@@ -943,6 +946,10 @@ def main():
         if (wg - lo) % 20 == 0:
             print("workgroup %d done, %d instructions so far, LDS accesses out of range: %d" % (wg, total, emu.lds_oob), flush=True)
     print("all workgroups done: %d wave instructions, LDS accesses out of range: %d" % (total, emu.lds_oob))
+    if "hist" in opts:      # how often each instruction ran: where a kernel's instructions go
+        with open(opts["hist"], "w") as hf:
+            for k, ins in enumerate(insts):
+                hf.write("%9d  %5d  %s\n" % (emu.executed.get(k, 0), ins.line, ins.text))
     if emu.lds_oob:
         return 1
     if len(args) > 2:
