@@ -78,6 +78,11 @@ struct Geom {
     static_assert(CHUNK >= P * ROW_MAX, "refill keeps up with the longest rows");
     static_assert(CHUNK >= 15 + AHEAD, "first refill covers the first period");
     static_assert(RING >= AHEAD + CHUNK + ROW_MAX + 8, "ring holds a row, a period ahead and a refill");
+    /* how much sooner than it must a stream may take its next chunk: the chunk goes CHUNK
+     * bytes behind the fill level modulo the ring, which has to stay behind the row being
+     * decoded (its start is at most ROW_MAX + 8 bytes before the record of the next period) */
+    static constexpr int EARLY = RING - CHUNK - ROW_MAX - 8 - AHEAD;
+    static_assert(EARLY >= 0, "a refill that is due is also allowed");
     static_assert(GPL == 2 && RING == 2 * CHUNK, "two granules per lane and refill, which never wrap inside one");
 };
 
@@ -593,7 +598,12 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                  * the stream.  What pf holds beyond the stream's last granule is left as it
                  * was: nothing that is decoded reads it. */
                 const uint32_t need = (bitpos >> 3) + need_lane;
-                if (fill < need) {
+                /* A stream must be topped up once its fill level is less than AHEAD beyond the
+                 * record of row r+3, and may be up to EARLY bytes sooner (the chunk then still
+                 * lands behind everything that is unread).  When any stream of the wave must,
+                 * all that may do: the streams of a wave then take their chunks in the same
+                 * periods instead of each in its own, and the other periods skip all this. */
+                if (wave_any(fill < need) && fill < need + G::EARLY) {
                     const uint32_t idx = fill & (RING - 1);
                     uint8_t* at = reinterpret_cast<uint8_t*>(ring) + idx;
                     *reinterpret_cast<u32x4*>(at) = pf[0];

@@ -60,6 +60,9 @@ __device__ __forceinline__ uint32_t pk_mad_u16_by_low(uint32_t a, uint32_t b, ui
     return d;
 }
 
+/* true in every lane if `mine` is true in any lane of the wave */
+__device__ __forceinline__ bool wave_any(bool mine) { return __builtin_amdgcn_ballot_w64(mine) != 0; }
+
 /* ---- LDS by 32-bit address ------------------------------------------------ */
 
 typedef __attribute__((address_space(3))) const uint32_t lds_const_u32;

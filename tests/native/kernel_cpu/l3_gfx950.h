@@ -54,6 +54,13 @@ inline uint32_t dpp_from_upper_lane(uint32_t v) {
     return l < 63 ? all[l + 1] : 0u;
 }
 inline uint32_t l3cpu_readfirstlane(uint32_t v) { return l3cpu::exchange(v)[0]; }
+/* a ballot over the wave: true if any lane's flag is */
+inline bool wave_any(bool mine) {
+    const uint32_t* all = l3cpu::exchange(mine ? 1u : 0u);
+    uint32_t any = 0;
+    for (int l = 0; l < 64; ++l) any |= all[l];
+    return any != 0;
+}
 
 /* v_pk_mad_i16: a * b + c in both 16-bit halves, modulo 2^16 */
 inline uint32_t pk_mad_i16(uint32_t a, uint32_t b, uint32_t c) {
