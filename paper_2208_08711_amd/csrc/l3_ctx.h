@@ -30,6 +30,7 @@ struct l3_ctx {
     uint16_t table_bits[768] = {};
     float table_key[7] = {};              /* mean, stdv, dtype it was worked out for */
     bool table_valid = false;
+    uint32_t resident_workgroups = 2048;  /* workgroups of a launch's last round (8 per CU) */
     uint16_t* static_table = nullptr;     /* device: this GPU's copy of the library's static table */
     hipEvent_t done[kSlots] = {};         /* the slot's kernels have finished */
     bool pending[kSlots] = {};

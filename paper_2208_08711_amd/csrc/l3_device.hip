@@ -150,7 +150,8 @@ __device__ __forceinline__ uint16_t normalised_bits(uint32_t v, float mean, floa
 template <int N, int PPL, int MODE>
 __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t unit,
                                             uint32_t* __restrict__ status, uint32_t crop_w,
-                                            uint32_t crop_h, const uint16_t* __restrict__ lut) {
+                                            uint32_t crop_h, const bool keeps_priority,
+                                            const uint16_t* __restrict__ lut) {
     using G = Geom<N, PPL>;
     constexpr int LPT = G::LPT, TPW = G::TPW, GPL = G::GPL, NW = G::NW, NP = G::NP, QW = G::QW;
     constexpr int CHUNK = G::CHUNK, RING = G::RING, P = G::P;
@@ -545,8 +546,12 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
 
     /* Waves that are ahead yield to waves that are behind (the hardware otherwise
      * favours the oldest wave, and the youngest ones would finish the kernel alone):
-     * the wave's issue priority drops by one in each quarter of its rows. */
-    const uint32_t quarter = (ph + 3) / 4;
+     * the wave's issue priority drops by one in each quarter of its rows.  That is for the
+     * workgroups that are resident when the launch ends.  A launch of several rounds of
+     * workgroups leaves the earlier ones at the top priority (keeps_priority): with the
+     * hardware's preference for the oldest wave they end one after the other instead of
+     * together, so their successors do not all wait for their first chunks at the same time. */
+    const uint32_t quarter = keeps_priority ? 0x7FFFFFFFu : (ph + 3) / 4;
     uint32_t next_drop = quarter, stage = 0;
     __builtin_amdgcn_s_setprio(3);
 
@@ -647,11 +652,12 @@ __device__ __forceinline__ const uint16_t* table_of(const uint16_t* lut, const L
 template <int N, int PPL, int MODE>
 __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel(
     const L3ImageDesc* __restrict__ descs, uint32_t units_per_image, uint32_t images,
-    uint32_t* __restrict__ status, uint32_t crop_w, uint32_t crop_h,
+    uint32_t* __restrict__ status, uint32_t crop_w, uint32_t crop_h, uint32_t top_priority_below,
     const uint16_t* __restrict__ lut, const typename TailFor<MODE>::type tail) {
     uint32_t image, unit;
     if (!take_work(units_per_image, images, image, unit)) return;
-    decode_unit<N, PPL, MODE>(descs[image], unit, status, crop_w, crop_h, table_of<MODE>(lut, tail));
+    decode_unit<N, PPL, MODE>(descs[image], unit, status, crop_w, crop_h, blockIdx.x < top_priority_below,
+                              table_of<MODE>(lut, tail));
 }
 
 /* ...or inside the kernel arguments: no upload, no dependency on a copy, so consecutive
@@ -665,11 +671,12 @@ static_assert(sizeof(DescPack<kArgDescs>) + sizeof(L3Table) + 64 <= 32768, "kern
 template <int N, int PPL, int MODE, int CAP>
 __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel_args(
     const DescPack<CAP> pack, uint32_t units_per_image, uint32_t images, uint32_t* __restrict__ status,
-    uint32_t crop_w, uint32_t crop_h, const uint16_t* __restrict__ lut,
+    uint32_t crop_w, uint32_t crop_h, uint32_t top_priority_below, const uint16_t* __restrict__ lut,
     const typename TailFor<MODE>::type tail) {
     uint32_t image, unit;
     if (!take_work(units_per_image, images, image, unit)) return;
-    decode_unit<N, PPL, MODE>(pack.d[image], unit, status, crop_w, crop_h, table_of<MODE>(lut, tail));
+    decode_unit<N, PPL, MODE>(pack.d[image], unit, status, crop_w, crop_h, blockIdx.x < top_priority_below,
+                              table_of<MODE>(lut, tail));
 }
 
 /* The table in device memory, for the call that keeps one there. */
@@ -976,11 +983,15 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
         /* one-dimensional grid, rounded up to a multiple of 8 (see take_work) */
         const auto grid_for = [gx](uint64_t images) { return (uint32_t)((gx * images + 7) / 8 * 8); };
         uint32_t gx_arg = gx;
+        /* the workgroups ahead of the launch's last round (see decode_unit's priorities) */
+        const uint32_t last_round = ctx->resident_workgroups;
+        const auto top_below = [last_round](uint32_t grid) { return grid > last_round ? grid - last_round : 0u; };
         if (in_args && count <= kArgDescsSmall) {
             DescPack<kArgDescsSmall> pack;
             std::memcpy(pack.d, stage + class_begin[k], (size_t)count * sizeof(L3ImageDesc));
             uint32_t count_arg = (uint32_t)count;
-            void* kernel_args[8] = {&pack, &gx_arg, &count_arg, &d_status, &crop_w, &crop_h, &table, tail};
+            uint32_t top_arg = top_below(grid_for((uint64_t)count));
+            void* kernel_args[9] = {&pack, &gx_arg, &count_arg, &d_status, &crop_w, &crop_h, &top_arg, &table, tail};
             if (hipLaunchKernel(pick_kernel(kClasses[k], mode).args_small, dim3(grid_for((uint64_t)count)),
                                 dim3(kBlockThreads), kernel_args, 0, stream) != hipSuccess)
                 return L3_ERR_DEVICE;
@@ -991,8 +1002,9 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
              * (which has kArgDescs spare entries behind the last descriptor), so that the
              * block is copied once, by the launch, and never sits on the stack */
             uint32_t count_arg = (uint32_t)count;
-            void* kernel_args[8] = {stage + class_begin[k], &gx_arg, &count_arg, &d_status,
-                                    &crop_w, &crop_h, &table, tail};
+            uint32_t top_arg = top_below(grid_for((uint64_t)count));
+            void* kernel_args[9] = {stage + class_begin[k], &gx_arg, &count_arg, &d_status,
+                                    &crop_w, &crop_h, &top_arg, &table, tail};
             if (hipLaunchKernel(pick_kernel(kClasses[k], mode).args, dim3(grid_for((uint64_t)count)),
                                 dim3(kBlockThreads), kernel_args, 0, stream) != hipSuccess)
                 return L3_ERR_DEVICE;
@@ -1005,7 +1017,8 @@ l3_status run_batch(l3_ctx* ctx, const l3_item* items, const l3_crop* crops, int
             const int m = count - first < per_launch ? count - first : per_launch;
             const L3ImageDesc* first_desc = d_descs + class_begin[k] + first;
             uint32_t m_arg = (uint32_t)m;
-            void* kernel_args[8] = {&first_desc, &gx_arg, &m_arg, &d_status, &crop_w, &crop_h, &table, tail};
+            uint32_t top_arg = top_below(grid_for((uint64_t)m));
+            void* kernel_args[9] = {&first_desc, &gx_arg, &m_arg, &d_status, &crop_w, &crop_h, &top_arg, &table, tail};
             if (hipLaunchKernel(kern, dim3(grid_for((uint64_t)m)), dim3(kBlockThreads), kernel_args, 0,
                                 stream) != hipSuccess)
                 return L3_ERR_DEVICE;
@@ -1041,6 +1054,15 @@ l3_status l3_ctx_create(l3_ctx** out, int device) {
         ctx->flat_order = !(e && e[0] == '0' && e[1] == 0);
     }
     ctx->static_table = static_table_of(device);
+    {
+        /* how many workgroups the launch's last round holds: eight per CU (what the local
+         * memory of the smallest-patch kernels allows; the others hold one or two more, which
+         * makes no difference to what the number is used for) */
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0)
+            cus = 256;
+        ctx->resident_workgroups = 8u * (uint32_t)cus;
+    }
     /* host staging for up to three full argument blocks, so that batches of that size never
      * make a call allocate */
     ctx->scratch_cap = 3 * kArgDescs;

@@ -387,6 +387,18 @@ class Emu:
         w.scc = int(sx < sy)
         self.ws(w, a[0], x if sx < sy else y)
 
+    def i_s_bcnt1_i32_b64(self, w, ins, a, m):
+        r = bin(self.rs64(w, a[1])).count("1")
+        self.ws(w, a[0], r)
+        w.scc = int(r != 0)
+
+    def i_s_bfe_u32(self, w, ins, a, m):
+        x, y = self.rs(w, a[1]), self.rs(w, a[2])
+        width = (y >> 16) & 0x7F
+        r = (x >> (y & 31)) & ((1 << width) - 1) & 0xFFFFFFFF
+        self.ws(w, a[0], r)
+        w.scc = int(r != 0)
+
     def i_s_lshl_b64(self, w, ins, a, m):
         r = (self.rs64(w, a[1]) << (self.rs(w, a[2]) & 63)) & 0xFFFFFFFFFFFFFFFF
         self.ws64(w, a[0], r)
@@ -518,6 +530,10 @@ class Emu:
     def i_v_xor_b32(self, w, ins, a, m): self.wv(w, a[0], self.rv(w, a[1]) ^ self.rv(w, a[2]))
     def i_v_max_u32(self, w, ins, a, m): self.wv(w, a[0], np.maximum(self.rv(w, a[1]), self.rv(w, a[2])))
     def i_v_min_u32(self, w, ins, a, m): self.wv(w, a[0], np.minimum(self.rv(w, a[1]), self.rv(w, a[2])))
+    def i_v_min3_u32(self, w, ins, a, m):
+        self.wv(w, a[0], np.minimum(np.minimum(self.rv(w, a[1]), self.rv(w, a[2])), self.rv(w, a[3])))
+    def i_v_max3_u32(self, w, ins, a, m):
+        self.wv(w, a[0], np.maximum(np.maximum(self.rv(w, a[1]), self.rv(w, a[2])), self.rv(w, a[3])))
     def i_v_add3_u32(self, w, ins, a, m): self.wv(w, a[0], self.rv(w, a[1]) + self.rv(w, a[2]) + self.rv(w, a[3]))
     def _sdwa_sel(self, x, sel):
         if sel in (None, "DWORD"):

@@ -161,6 +161,8 @@ constexpr unsigned hipEventDisableTiming = 2, hipHostMallocDefault = 0;
 inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
 inline hipError_t hipSetDevice(int) { return hipSuccess; }
 inline hipError_t hipGetDeviceCount(int* n) { *n = 1; return hipSuccess; }
+enum hipDeviceAttribute_t { hipDeviceAttributeMultiprocessorCount = 63 };
+inline hipError_t hipDeviceGetAttribute(int* v, hipDeviceAttribute_t, int) { *v = 1; return hipSuccess; }   /* one CU: launches of more than 8 workgroups have early rounds */
 inline hipError_t hipMalloc(void** p, size_t n) {
     *p = std::malloc(n ? n : 1);
     if (*p) l3cpu::regions()[*p] = n;

@@ -34,7 +34,7 @@ namespace {
 
 /* what a recorded launch says about its kernel: patch size, mode, how the descriptors travel
  * (0 device table, 1 up to 32 in the arguments, 2 up to 256), and the sizes of its first and
- * last argument (the others are gx, count, status, crop_w, crop_h, table pointer) */
+ * last argument (the others are gx, count, status, crop_w, crop_h, top_priority_below, table pointer) */
 struct KernelFacts { int n, mode, kind; size_t first_bytes, tail_bytes; };
 std::map<const void*, KernelFacts> g_facts;
 int g_recorded = 0;
@@ -57,7 +57,7 @@ void record_launch(const char* dir, const void* kernel, dim3 grid, dim3 block, v
     const int32_t head[6] = {k.n, k.mode, k.kind, (int32_t)grid.x, (int32_t)block.x, 0};
     std::fwrite(head, 4, 6, f);
     /* the argument block as the GPU sees it: every argument at its natural alignment */
-    std::vector<uint8_t> block_bytes(k.first_bytes + 32 + k.tail_bytes, 0);
+    std::vector<uint8_t> block_bytes(k.first_bytes + 40 + k.tail_bytes, 0);
     std::memcpy(block_bytes.data(), a[0], k.first_bytes);
     const size_t o = k.first_bytes;
     std::memcpy(&block_bytes[o], a[1], 4);
@@ -65,8 +65,9 @@ void record_launch(const char* dir, const void* kernel, dim3 grid, dim3 block, v
     std::memcpy(&block_bytes[o + 8], a[3], 8);
     std::memcpy(&block_bytes[o + 16], a[4], 4);
     std::memcpy(&block_bytes[o + 20], a[5], 4);
-    std::memcpy(&block_bytes[o + 24], a[6], 8);
-    std::memcpy(&block_bytes[o + 32], a[7], k.tail_bytes);
+    std::memcpy(&block_bytes[o + 24], a[6], 4);
+    std::memcpy(&block_bytes[o + 32], a[7], 8);
+    std::memcpy(&block_bytes[o + 40], a[8], k.tail_bytes);
     const uint64_t bytes = block_bytes.size();
     std::fwrite(&bytes, 8, 1, f);
     std::fwrite(block_bytes.data(), 1, bytes, f);
@@ -87,19 +88,22 @@ void register_kernels() {
         l3_decode_kernel<N, 4, MODE>(*static_cast<const L3ImageDesc**>(a[0]), *static_cast<uint32_t*>(a[1]),
                                      *static_cast<uint32_t*>(a[2]), *static_cast<uint32_t**>(a[3]),
                                      *static_cast<uint32_t*>(a[4]), *static_cast<uint32_t*>(a[5]),
-                                     *static_cast<const uint16_t**>(a[6]), *static_cast<Tail*>(a[7]));
+                                     *static_cast<uint32_t*>(a[6]), *static_cast<const uint16_t**>(a[7]),
+                                     *static_cast<Tail*>(a[8]));
     };
     reg[reinterpret_cast<const void*>(&l3_decode_kernel_args<N, 4, MODE, kArgDescsSmall>)] = [](void** a) {
         l3_decode_kernel_args<N, 4, MODE, kArgDescsSmall>(
             *static_cast<DescPack<kArgDescsSmall>*>(a[0]), *static_cast<uint32_t*>(a[1]),
             *static_cast<uint32_t*>(a[2]), *static_cast<uint32_t**>(a[3]), *static_cast<uint32_t*>(a[4]),
-            *static_cast<uint32_t*>(a[5]), *static_cast<const uint16_t**>(a[6]), *static_cast<Tail*>(a[7]));
+            *static_cast<uint32_t*>(a[5]), *static_cast<uint32_t*>(a[6]), *static_cast<const uint16_t**>(a[7]),
+            *static_cast<Tail*>(a[8]));
     };
     reg[reinterpret_cast<const void*>(&l3_decode_kernel_args<N, 4, MODE, kArgDescs>)] = [](void** a) {
         l3_decode_kernel_args<N, 4, MODE, kArgDescs>(
             *static_cast<DescPack<kArgDescs>*>(a[0]), *static_cast<uint32_t*>(a[1]),
             *static_cast<uint32_t*>(a[2]), *static_cast<uint32_t**>(a[3]), *static_cast<uint32_t*>(a[4]),
-            *static_cast<uint32_t*>(a[5]), *static_cast<const uint16_t**>(a[6]), *static_cast<Tail*>(a[7]));
+            *static_cast<uint32_t*>(a[5]), *static_cast<uint32_t*>(a[6]), *static_cast<const uint16_t**>(a[7]),
+            *static_cast<Tail*>(a[8]));
     };
 }
 template <int N>

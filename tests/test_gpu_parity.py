@@ -422,6 +422,15 @@ def test_fused_crop_normalize_config5(l3, ctx):
     tensor_case(l3, ctx, images[:6], crops[:6], 224, 1)
 
 
+def test_fused_call_with_more_images_than_the_argument_block_holds(l3, ctx):
+    """300 small images: the descriptors go through the table in device memory, the normalised
+    values still through the kernel's arguments; both output types, mirrored and not."""
+    images = [synth.gradient_noise(5200 + k, 40 + (k % 9), 36 + (k % 4), 2.0) for k in range(300)]
+    crops = [(k % 9, k % 5, k & 1) for k in range(300)]
+    tensor_case(l3, ctx, images, crops, 32, 0, patch=32)
+    tensor_case(l3, ctx, images, crops, 32, 1, patch=32, mean=(0.3, 0.4, 0.5), stdv=(0.5, 0.25, 2.0))
+
+
 def test_fused_constants_change_between_calls(l3, ctx):
     """The normalisation table is kept between calls: ten calls on one context that
     alternate between three sets of constants and the two output types must each use

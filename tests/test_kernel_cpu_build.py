@@ -120,6 +120,12 @@ def test_more_than_256_images_go_through_the_descriptor_table(exes):
     case = os.path.join(exes["tmp"], "many.bin")
     write_case(case, 0, images, 32)
     run(exes["asan"], case)
+    # the fused kernel of that kind takes its descriptors from the table in device memory and
+    # its normalised values from the tail of its arguments
+    images = [synth.uniform_bytes(3100 + k, 20 + k % 7, 18 + k % 5) for k in range(260)]
+    case = os.path.join(exes["tmp"], "many_fused.bin")
+    write_case(case, 2, images, 32, crops=[(k % 5, k % 3, k & 1) for k in range(260)], crop=(16, 15))
+    run(exes["asan"], case)
 
 
 @pytest.mark.parametrize("patch,mode", [(32, 0), (64, 0), (128, 0), (128, 1), (32, 2)])
