@@ -151,6 +151,7 @@ template <int N, int PPL, int MODE>
 __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t unit,
                                             uint32_t* __restrict__ status, uint32_t crop_w,
                                             uint32_t crop_h, const bool keeps_priority,
+                                            const uint32_t age_rank,
                                             const uint16_t* __restrict__ lut) {
     using G = Geom<N, PPL>;
     constexpr int LPT = G::LPT, TPW = G::TPW, GPL = G::GPL, NW = G::NW, NP = G::NP, QW = G::QW;
@@ -546,13 +547,18 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
 
     /* Waves that are ahead yield to waves that are behind (the hardware otherwise
      * favours the oldest wave, and the youngest ones would finish the kernel alone):
-     * the wave's issue priority drops by one in each quarter of its rows.  That is for the
-     * workgroups that are resident when the launch ends.  A launch of several rounds of
-     * workgroups leaves the earlier ones at the top priority (keeps_priority): with the
-     * hardware's preference for the oldest wave they end one after the other instead of
-     * together, so their successors do not all wait for their first chunks at the same time. */
-    const uint32_t quarter = keeps_priority ? 0x7FFFFFFFu : (ph + 3) / 4;
-    uint32_t next_drop = quarter, stage = 0;
+     * the wave's issue priority drops by one in each quarter of its rows.  Among waves of
+     * equal priority the oldest still wins, so an older workgroup drops a little sooner
+     * than a younger one: after (8 k + age_rank) / 32 of its rows, k = 1, 2, 3, where
+     * age_rank is 0 for the oldest of the (up to eight) workgroups of a CU and 7 for the
+     * youngest.  That is for the workgroups that are resident when the launch ends.  A
+     * launch of several rounds of workgroups leaves the earlier ones at the top priority
+     * (keeps_priority): with the hardware's preference for the oldest wave they end one
+     * after the other instead of together, so their successors do not all wait for their
+     * first chunks at the same time. */
+    const uint32_t drop_at[3] = {keeps_priority ? 0x7FFFFFFFu : (ph * (8u + age_rank) + 31u) / 32u,
+                                 (ph * (16u + age_rank) + 31u) / 32u, (ph * (24u + age_rank) + 31u) / 32u};
+    uint32_t next_drop = drop_at[0], stage = 0;
     __builtin_amdgcn_s_setprio(3);
 
     /* Periods of P = 3 rows, unrolled so that the row's place in the period is a
@@ -569,8 +575,8 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     for (uint32_t r = 0; r < ph; r += P) {
         const uint32_t rows = min((uint32_t)P, ph - r);
         if (r >= next_drop) {
-            next_drop += quarter;
             ++stage;
+            next_drop = stage == 1 ? drop_at[1] : (stage == 2 ? drop_at[2] : 0x7FFFFFFFu);
             if (stage == 1) __builtin_amdgcn_s_setprio(2);
             else if (stage == 2) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
@@ -639,6 +645,15 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
     if (flags && active && status) atomicOr(&status[d.status_index], flags);
 }
 
+/* How old a workgroup of the launch's last round is among the workgroups of its CU, 0 (oldest)
+ * to 7: workgroups are handed out in the order of their numbers, to the XCDs in turn and inside
+ * an XCD to its 32 CUs in turn, so the n-th workgroup of an XCD is about the (n / 32)-th of
+ * its CU.  Only steers issue priorities. */
+__device__ __forceinline__ uint32_t age_rank_of(uint32_t top_priority_below) {
+    const uint32_t nth = (blockIdx.x - min(blockIdx.x, top_priority_below)) >> 3;
+    return min(7u, nth / 32u);
+}
+
 /* Where a fused kernel reads its table: in device memory if the call gave one, else in its
  * own arguments (the argument segment is ordinary device memory). */
 template <int MODE>
@@ -657,7 +672,7 @@ __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel(
     uint32_t image, unit;
     if (!take_work(units_per_image, images, image, unit)) return;
     decode_unit<N, PPL, MODE>(descs[image], unit, status, crop_w, crop_h, blockIdx.x < top_priority_below,
-                              table_of<MODE>(lut, tail));
+                              age_rank_of(top_priority_below), table_of<MODE>(lut, tail));
 }
 
 /* ...or inside the kernel arguments: no upload, no dependency on a copy, so consecutive
@@ -676,7 +691,7 @@ __global__ __launch_bounds__(kBlockThreads) void l3_decode_kernel_args(
     uint32_t image, unit;
     if (!take_work(units_per_image, images, image, unit)) return;
     decode_unit<N, PPL, MODE>(pack.d[image], unit, status, crop_w, crop_h, blockIdx.x < top_priority_below,
-                              table_of<MODE>(lut, tail));
+                              age_rank_of(top_priority_below), table_of<MODE>(lut, tail));
 }
 
 /* The table in device memory, for the call that keeps one there. */

@@ -387,6 +387,9 @@ class Emu:
         w.scc = int(sx < sy)
         self.ws(w, a[0], x if sx < sy else y)
 
+    def i_s_brev_b32(self, w, ins, a, m):
+        self.ws(w, a[0], int("{:032b}".format(self.rs(w, a[1]))[::-1], 2))
+
     def i_s_bcnt1_i32_b64(self, w, ins, a, m):
         r = bin(self.rs64(w, a[1])).count("1")
         self.ws(w, a[0], r)
