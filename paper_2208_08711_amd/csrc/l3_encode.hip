@@ -399,8 +399,25 @@ __device__ __forceinline__ void encode_strip(const L3EncodeDesc& d, uint32_t* __
         const u32x3 zero = {0, 0, 0};
         ahead[i] = (uint32_t)i < ph ? load_row(src + i * row_stride) : zero;
     }
+    /* issue priorities as in the decoder: lowered by quarters of the rows, an older
+     * workgroup of a CU a little sooner; workgroups ahead of the launch's last round keep
+     * the top priority */
+    const uint32_t wg = blockIdx.y * gridDim.x + blockIdx.x, wgs = gridDim.x * gridDim.y;
+    const uint32_t last_round_from = wgs > 2048u ? wgs - 2048u : 0u;
+    const uint32_t age_rank = min(7u, ((wg - min(wg, last_round_from)) >> 3) / 32u);
+    const uint32_t drop_at[3] = {wg < last_round_from ? 0x7FFFFFFFu : (ph * (8u + age_rank) + 31u) / 32u,
+                                 (ph * (16u + age_rank) + 31u) / 32u, (ph * (24u + age_rank) + 31u) / 32u};
+    uint32_t next_drop = drop_at[0], stage = 0;
+    __builtin_amdgcn_s_setprio(3);
     for (uint32_t r = 0; r < ph; r += P) {
         const uint32_t rows = min((uint32_t)P, ph - r);
+        if (r >= next_drop) {
+            ++stage;
+            next_drop = stage == 1 ? drop_at[1] : (stage == 2 ? drop_at[2] : 0x7FFFFFFFu);
+            if (stage == 1) __builtin_amdgcn_s_setprio(2);
+            else if (stage == 2) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         u32x3 raw[P];
 #pragma unroll
         for (int i = 0; i < P; ++i) raw[i] = ahead[i];
