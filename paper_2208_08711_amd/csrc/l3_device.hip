@@ -77,12 +77,13 @@ struct Geom {
     static_assert(GPL * LPT * 16 == CHUNK && GPL >= 1, "chunk is a whole number of granule rounds");
     static_assert(CHUNK >= P * ROW_MAX, "refill keeps up with the longest rows");
     static_assert(CHUNK >= 15 + AHEAD, "first refill covers the first period");
+    static_assert(CHUNK >= 15 + P * ROW_MAX + AHEAD, "no refill is due in the first period");
     static_assert(RING >= AHEAD + CHUNK + ROW_MAX + 8, "ring holds a row, a period ahead and a refill");
     /* how much sooner than it must a stream may take its next chunk: the chunk goes CHUNK
      * bytes behind the fill level modulo the ring, which has to stay behind the row being
      * decoded (its start is at most ROW_MAX + 8 bytes before the record of the next period) */
     static constexpr int EARLY = RING - CHUNK - ROW_MAX - 8 - AHEAD;
-    static_assert(EARLY >= 0, "a refill that is due is also allowed");
+    static_assert(EARLY >= 1, "a refill that is due is also allowed");
     static_assert(GPL == 2 && RING == 2 * CHUNK, "two granules per lane and refill, which never wrap inside one");
 };
 
@@ -251,8 +252,10 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
             if (idx == 0) *reinterpret_cast<u32x4*>(reinterpret_cast<uint8_t*>(ring) + RING) = pf[t];
         }
         fill = CHUNK + xl * 16;   /* this lane's first granule of the chunk in pf: see the ring top-up */
+        /* the second chunk is asked for in the first period, not here, where every workgroup
+         * of the launch waits for its first one */
 #pragma unroll
-        for (int t = 0; t < GPL; ++t) pf[t] = load_granule(origin, CHUNK + (t * LPT + xl) * 16, limit);
+        for (int t = 0; t < GPL; ++t) pf[t] = u32x4{0, 0, 0, 0};
     }
     if (MODE == L3_MODE_TENSOR) {
 #pragma unroll
@@ -405,9 +408,8 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                 if (row >= 0 && row < (int32_t)crop_h && nvalid) {
                     const int32_t col0 = (int32_t)x - win_x0;   /* window column of pixel 0 */
                     const bool whole = nvalid == 4 && col0 >= 0 && col0 + 4 <= (int32_t)crop_w;
-                    /* all twelve table reads first, so that they travel together; each lands
-                     * in the half of the register it is stored from (elements 0|1 and 2|3 of
-                     * the word), so nothing has to be packed afterwards */
+                    /* all twelve table reads first, so that they travel together; elements
+                     * 0|1 and 2|3 of the word then share a register (one byte permute each) */
                     u16x2 q[3][2];
 #pragma unroll
                     for (int ch = 0; ch < 3; ++ch) {
@@ -571,7 +573,9 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
      * tenant of the buffer.  (With two buffers a wave could still be writing out period
      * k-2 when an early one starts to park period k.) */
     uint32_t buf = 0, prev_buf = 0;
-    const uint32_t need_lane = G::AHEAD + xl * 16;   /* see the ring top-up */
+    /* see the ring top-up: the bit position up to which the record of the next period may
+     * lie before this lane's stream must take its next chunk, 8 * (fill - AHEAD - 16 xl) */
+    uint32_t reach = (fill - (G::AHEAD + xl * 16)) * 8;
     for (uint32_t r = 0; r < ph; r += P) {
         const uint32_t rows = min((uint32_t)P, ph - r);
         if (r >= next_drop) {
@@ -608,19 +612,27 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                  * lane's second granule sits CHUNK / 2 behind its first, in the ring and in
                  * the stream.  What pf holds beyond the stream's last granule is left as it
                  * was: nothing that is decoded reads it. */
-                const uint32_t need = (bitpos >> 3) + need_lane;
                 /* A stream must be topped up once its fill level is less than AHEAD beyond the
-                 * record of row r+3, and may be up to EARLY bytes sooner (the chunk then still
-                 * lands behind everything that is unread).  When any stream of the wave must,
-                 * all that may do: the streams of a wave then take their chunks in the same
-                 * periods instead of each in its own, and the other periods skip all this. */
-                if (wave_any(fill < need) && fill < need + G::EARLY) {
+                 * record of row r+3 (bitpos beyond `reach`; the comparison in bits asks for it
+                 * up to 7 bits sooner than one in bytes would), and may be up to EARLY bytes
+                 * sooner (the chunk then still lands behind everything that is unread; one
+                 * byte of that is given away to the comparison in bits).  When any stream of
+                 * the wave must, all that may do: the streams of a wave then take their chunks
+                 * in the same periods instead of each in its own, and the other periods skip
+                 * all this.  The first period instead asks for the chunk behind the first one:
+                 * its top-up is never due (the first chunk reaches AHEAD beyond the record of
+                 * row 3 from any start alignment, see Geom). */
+                if (r == 0) {
+#pragma unroll
+                    for (int t = 0; t < GPL; ++t) pf[t] = load_granule(origin, CHUNK + (t * LPT + xl) * 16, limit);
+                } else if (wave_any(reach < bitpos) && reach < bitpos + 8 * (G::EARLY - 1)) {
                     const uint32_t idx = fill & (RING - 1);
                     uint8_t* at = reinterpret_cast<uint8_t*>(ring) + idx;
                     *reinterpret_cast<u32x4*>(at) = pf[0];
                     *reinterpret_cast<u32x4*>(at + CHUNK / 2) = pf[1];
                     if (idx == 0) *reinterpret_cast<u32x4*>(at + RING) = pf[0];
                     fill += CHUNK;
+                    reach += 8 * CHUNK;
                     if (fill < limit)
                         pf[0] = *reinterpret_cast<global_const_u32x4*>((uintptr_t)(origin + fill));
                     if (fill + CHUNK / 2 < limit)
