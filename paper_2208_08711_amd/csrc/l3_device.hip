@@ -337,6 +337,17 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
         word_off[pass] = (MODE == L3_MODE_HWC ? 3u : 1u) * word_x[pass] +
                          (ty - ty_base) * (uint32_t)N * (uint32_t)out_row_stride;
     }
+    /* tensor mode: whether the word's 4 pixels all lie inside the window, and the byte offset
+     * of its 4 elements in a row of the window (mirrored or not): the same for every row */
+    bool tensor_whole[NW];
+    uint32_t tensor_at[NW];
+#pragma unroll
+    for (int pass = 0; pass < NW; ++pass) {
+        const int32_t col0 = (int32_t)word_x[pass] - win_x0;
+        tensor_whole[pass] = MODE == L3_MODE_TENSOR && word_valid[pass] == 4 && col0 >= 0 &&
+                             col0 + 4 <= (int32_t)crop_w;
+        tensor_at[pass] = 2u * (uint32_t)(win_flip ? (int32_t)crop_w - 4 - col0 : col0);
+    }
 
     /* After the workgroup barrier: this wave writes row c of the period whose rows
      * are parked in buffer `buf` (rows first .. first+count-1 of the patch).  Lane l
@@ -406,41 +417,46 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                  * window's edge go element by element. */
                 const int32_t row = (int32_t)y - win_y0;
                 if (row >= 0 && row < (int32_t)crop_h && nvalid) {
-                    const int32_t col0 = (int32_t)x - win_x0;   /* window column of pixel 0 */
-                    const bool whole = nvalid == 4 && col0 >= 0 && col0 + 4 <= (int32_t)crop_w;
-                    /* all twelve table reads first, so that they travel together; elements
-                     * 0|1 and 2|3 of the word then share a register (one byte permute each) */
-                    u16x2 q[3][2];
+                    /* all twelve table reads first, so that they travel together */
+                    uint16_t e[3][4];
 #pragma unroll
                     for (int ch = 0; ch < 3; ++ch) {
                         const uint32_t word = ch == 0 ? pr : (ch == 1 ? pg : pb);
-                        q[ch][0].x = s_lut[ch * 256 + (word & 0xFFu)];
-                        q[ch][0].y = s_lut[ch * 256 + ((word >> 8) & 0xFFu)];
-                        q[ch][1].x = s_lut[ch * 256 + ((word >> 16) & 0xFFu)];
-                        q[ch][1].y = s_lut[ch * 256 + (word >> 24)];
-                    }
-                    /* element (ch, row, 0) of this image; planes are crop_h * crop_w apart */
-                    global_u16* line = reinterpret_cast<global_u16*>((uintptr_t)out_base) + (size_t)row * crop_w;
-                    const size_t plane = (size_t)crop_h * crop_w;
-                    if (whole) {
-                        uint32_t col = (uint32_t)(win_flip ? (int32_t)crop_w - 4 - col0 : col0);
-                        L3_KEEP_VGPR(col);      /* stays the store's 32-bit offset */
 #pragma unroll
-                        for (int ch = 0; ch < 3; ++ch) {
-                            const uint32_t e01 = __builtin_bit_cast(uint32_t, q[ch][0]);
-                            const uint32_t e23 = __builtin_bit_cast(uint32_t, q[ch][1]);
-                            u32x2 v;
-                            if (win_flip) {               /* the same for the whole image: 3 2 | 1 0 */
-                                v.x = __builtin_amdgcn_alignbit(e23, e23, 16);
-                                v.y = __builtin_amdgcn_alignbit(e01, e01, 16);
-                            } else {
-                                v.x = e01;
-                                v.y = e23;
+                        for (int k = 0; k < 4; ++k) e[ch][k] = s_lut[ch * 256 + ((word >> (8 * k)) & 0xFFu)];
+                    }
+                    /* element (ch, row, 0) of this image; planes are crop_h * crop_w apart: the
+                     * planes' rows start at scalar addresses, the lane adds its byte offset */
+                    const size_t plane = (size_t)crop_h * crop_w;
+                    if (tensor_whole[pass]) {
+                        if (win_flip) {        /* the same for the whole image: elements 3 2 | 1 0 */
+#pragma unroll
+                            for (int ch = 0; ch < 3; ++ch) {
+                                uint64_t line_at = out_base + 2 * ((uint64_t)row * crop_w + ch * plane);
+                                L3_KEEP_SGPR(line_at);
+                                global_u8* line = reinterpret_cast<global_u8*>((uintptr_t)line_at);
+                                uint32_t at = tensor_at[pass];
+                                L3_KEEP_VGPR(at);      /* stays the store's 32-bit offset */
+                                const u16x2 lo = {e[ch][3], e[ch][2]}, hi = {e[ch][1], e[ch][0]};
+                                const u32x2 v = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                                __builtin_nontemporal_store(v, reinterpret_cast<global_u32x2_any*>(line + at));
                             }
-                            __builtin_nontemporal_store(
-                                v, reinterpret_cast<global_u32x2_any*>(line + ch * plane + col));
+                        } else {
+#pragma unroll
+                            for (int ch = 0; ch < 3; ++ch) {
+                                uint64_t line_at = out_base + 2 * ((uint64_t)row * crop_w + ch * plane);
+                                L3_KEEP_SGPR(line_at);
+                                global_u8* line = reinterpret_cast<global_u8*>((uintptr_t)line_at);
+                                uint32_t at = tensor_at[pass];
+                                L3_KEEP_VGPR(at);      /* stays the store's 32-bit offset */
+                                const u16x2 lo = {e[ch][0], e[ch][1]}, hi = {e[ch][2], e[ch][3]};
+                                const u32x2 v = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                                __builtin_nontemporal_store(v, reinterpret_cast<global_u32x2_any*>(line + at));
+                            }
                         }
                     } else {
+                        const int32_t col0 = (int32_t)x - win_x0;   /* window column of pixel 0 */
+                        global_u16* line = reinterpret_cast<global_u16*>((uintptr_t)out_base) + (size_t)row * crop_w;
 #pragma unroll
                         for (int ch = 0; ch < 3; ++ch) {
                             global_u16* out16 = line + ch * plane;
@@ -449,7 +465,7 @@ __device__ __forceinline__ void decode_unit(const L3ImageDesc& d, const uint32_t
                                 int32_t col = col0 + k;
                                 if ((uint32_t)k < nvalid && col >= 0 && col < (int32_t)crop_w) {
                                     if (win_flip) col = (int32_t)crop_w - 1 - col;
-                                    out16[col] = (k & 1) ? q[ch][k / 2].y : q[ch][k / 2].x;
+                                    out16[col] = e[ch][k];
                                 }
                             }
                         }
